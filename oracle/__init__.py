@@ -1,0 +1,150 @@
+"""CPU oracle for 1-D / 2-D valid convolution -- TEST INFRASTRUCTURE ONLY.
+
+A thin numpy/ctypes wrapper over ``conv_oracle.c`` (plain C, fp64 sums), which
+writes out the paper's Eq. 2 (Section 3.1) and Eq. 3 (Section 5) as loops.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  The GPU library never does, and this
+package never imports the GPU library.
+
+Pins (see ``tests/test_oracle_pins.py`` and ``tests/test_ure_recurrences.py``):
+hand-expanded sums, delta filters, linearity, separability, constant / ramp /
+box closed forms, integer-exact data, numpy's and torch's float64 routines as a
+library special case, the paper's recurrence equations (Section 3.1, Table 2,
+Section 5) evaluated literally, and the printed values of Table 4.
+Nothing here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "conv_oracle.c")
+_LIB = os.path.join(_HERE, "libconv_oracle.so")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile conv_oracle.c with gcc (no fast-math: summation order is kept)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        fp = ctypes.POINTER(ctypes.c_float)
+        dp = ctypes.POINTER(ctypes.c_double)
+        for name in ("oracle_conv1d", "oracle_absdot1d"):
+            fn = getattr(lib, name)
+            fn.argtypes = [fp, ctypes.c_size_t, fp, ctypes.c_int, dp, ctypes.c_int]
+            fn.restype = ctypes.c_int
+        for name in ("oracle_conv2d", "oracle_absdot2d"):
+            fn = getattr(lib, name)
+            fn.argtypes = [fp, ctypes.c_int, ctypes.c_int, ctypes.c_size_t,
+                           fp, ctypes.c_int, ctypes.c_int,
+                           dp, ctypes.c_size_t, ctypes.c_int]
+            fn.restype = ctypes.c_int
+        lib.oracle_threads.argtypes = [ctypes.c_int]
+        lib.oracle_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _f32(a, ndim):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if a.ndim != ndim:
+        raise ValueError(f"expected {ndim}-D array, got shape {a.shape}")
+    return a
+
+
+def _fptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _dptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def threads_used(nthreads: int) -> int:
+    return int(_load().oracle_threads(int(nthreads)))
+
+
+def _run1d(fname, x, w, nthreads):
+    x = _f32(x, 1)
+    w = _f32(w, 1)
+    n, k = x.shape[0], w.shape[0]
+    if k < 1 or k > n:
+        raise ValueError("need 1 <= k <= n")
+    y = np.empty(n - k + 1, dtype=np.float64)
+    rc = getattr(_load(), fname)(_fptr(x), n, _fptr(w), k, _dptr(y), int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"{fname} failed with status {rc}")
+    return y
+
+
+def _run2d(fname, x, f, nthreads):
+    x = _f32(x, 2)
+    f = _f32(f, 2)
+    h, w_img = x.shape
+    kh, kw = f.shape
+    if kh < 1 or kw < 1 or kh > h or kw > w_img:
+        raise ValueError("filter must fit inside the image")
+    y = np.empty((h - kh + 1, w_img - kw + 1), dtype=np.float64)
+    rc = getattr(_load(), fname)(_fptr(x), h, w_img, w_img, _fptr(f), kh, kw,
+                                 _dptr(y), y.shape[1], int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"{fname} failed with status {rc}")
+    return y
+
+
+def conv1d(x, w, nthreads: int = 1) -> np.ndarray:
+    """Eq. 2: y[c] = sum_q x[c+q] * w[q]; fp32 inputs, fp64 result, length n-k+1."""
+    return _run1d("oracle_conv1d", x, w, nthreads)
+
+
+def conv2d(x, f, nthreads: int = 1) -> np.ndarray:
+    """Eq. 3 on a row-major image: y[r][c] = sum_p sum_q f[p][q] * x[r+p][c+q]."""
+    return _run2d("oracle_conv2d", x, f, nthreads)
+
+
+def absdot1d(x, w, nthreads: int = 1) -> np.ndarray:
+    """sum_q |x[c+q]| |w[q]| -- the scale of the parity metric."""
+    return _run1d("oracle_absdot1d", x, w, nthreads)
+
+
+def absdot2d(x, f, nthreads: int = 1) -> np.ndarray:
+    return _run2d("oracle_absdot2d", x, f, nthreads)
+
+
+def max_rel_err(y_test, y_ref, scale) -> float:
+    """max_i |y_test[i] - y_ref[i]| / scale[i]   (all compared in fp64).
+
+    Where scale[i] == 0 every term of the sum is zero, so the only acceptable
+    difference is exactly 0; anything else is reported as infinity.
+    """
+    y_test = np.asarray(y_test, dtype=np.float64)
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    scale = np.asarray(scale, dtype=np.float64)
+    if y_test.shape != y_ref.shape or y_ref.shape != scale.shape:
+        raise ValueError(f"shape mismatch {y_test.shape} {y_ref.shape} {scale.shape}")
+    if y_test.size == 0:
+        return 0.0
+    diff = np.abs(y_test - y_ref)
+    if not np.all(np.isfinite(y_test)):
+        return float("inf")
+    zero = scale == 0
+    if np.any(diff[zero] != 0):
+        return float("inf")
+    safe = np.where(zero, 1.0, scale)
+    return float(np.max(np.where(zero, 0.0, diff / safe)))

@@ -1,0 +1,115 @@
+"""Space-time transforms of the paper's systolic designs and its analytical model.
+
+A design maps an iteration point (c, q) -- output position c, tap q -- to a
+processing element P.z and a time step s^T.z (paper Section 2.2).  The table
+below restates the transforms of Section 3.1 (SBM) and Table 2 (the other
+five), and ``model`` evaluates the paper's Section 6.2 model:
+
+    outturn     = outputs / #time steps
+    utilisation = outputs * taps / (#lanes * #time steps)
+
+where #lanes is the length of the *virtual* PE vector (the extent of P.z) and
+#time steps the extent of s^T.z.  With 16 outputs and 5 taps this reproduces
+the paper's Table 4.
+
+``wave64`` evaluates the same two figures for the way the HIP kernels lay a
+design over a 64-lane wavefront with a 4-float tile per lane.
+
+Host-side bookkeeping only: no convolution arithmetic lives here.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, Tuple
+
+
+@dataclass(frozen=True)
+class Transform:
+    """Rows of the 2x2 transform matrix over (c, q): allocation P and schedule s."""
+    alloc: Tuple[int, int]
+    sched: Tuple[int, int]
+
+    @property
+    def det(self) -> int:
+        return self.alloc[0] * self.sched[1] - self.alloc[1] * self.sched[0]
+
+
+# (input, weight, partial sum) naming of Section 3.1: Broadcast / Forwarded / Stay,
+# Migrated / Sedimented.
+TRANSFORMS: Dict[str, Transform] = {
+    "SBM": Transform((1, 1), (0, 1)),    # s = c + q, t = q        (Section 3.1)
+    "BSM": Transform((0, 1), (1, 1)),    # s = q,     t = c + q    (Table 2, row 1 left)
+    "FSM": Transform((0, 1), (1, -1)),   # s = q,     t = c - q    (Table 2, row 1 right)
+    "BFS": Transform((1, 0), (1, 1)),    # s = c,     t = c + q    (Table 2, row 2 left)
+    "FFS": Transform((1, 0), (2, 1)),    # s = c,     t = 2c + q   (Table 2, row 2 right)
+    "FBS": Transform((1, 0), (0, 1)),    # s = c,     t = q        (Table 2, row 3 left)
+}
+
+# Dependence vectors e (a variable at z reads its value from z - e), per design.
+# None = the variable is loaded / broadcast, not passed between iterations.
+DEPENDENCES: Dict[str, Dict[str, Tuple[int, int]]] = {
+    "SBM": {"X": (-1, 1), "Z": (0, 1)},
+    "FBS": {"X": (-1, 1), "Z": (0, 1)},
+    "BSM": {"W": (1, 0), "Z": (0, 1)},
+    "BFS": {"W": (1, 0), "Z": (0, 1)},
+    "FSM": {"X": (1, -1), "W": (1, 0), "Z": (0, -1)},
+    "FFS": {"X": (1, -1), "W": (1, 0), "Z": (0, 1)},
+}
+
+
+def extent(row: Tuple[int, int], n_out: int, n_taps: int) -> int:
+    """Number of distinct values of row.(c, q) over 0<=c<n_out, 0<=q<n_taps."""
+    return abs(row[0]) * (n_out - 1) + abs(row[1]) * (n_taps - 1) + 1
+
+
+def is_valid(design: str) -> bool:
+    """Section 2.2: every dependence needs s^T e >= 0 and != 0 (none of the
+    passed variables is a broadcast); two points on one PE must differ in
+    time, i.e. the transform must not be singular."""
+    t = TRANSFORMS[design]
+    if t.det == 0:
+        return False
+    for e in DEPENDENCES[design].values():
+        if t.sched[0] * e[0] + t.sched[1] * e[1] <= 0:
+            return False
+    return True
+
+
+def movement(design: str) -> Dict[str, Tuple[int, int]]:
+    """(space distance P.e, time distance s^T e) of every passed variable."""
+    t = TRANSFORMS[design]
+    return {v: (t.alloc[0] * e[0] + t.alloc[1] * e[1], t.sched[0] * e[0] + t.sched[1] * e[1])
+            for v, e in DEPENDENCES[design].items()}
+
+
+def model(design: str, n_out: int = 16, n_taps: int = 5) -> Dict[str, float]:
+    t = TRANSFORMS[design]
+    lanes = extent(t.alloc, n_out, n_taps)
+    steps = extent(t.sched, n_out, n_taps)
+    return {
+        "lanes": lanes,
+        "steps": steps,
+        "outturn": n_out / steps,
+        "utilisation": n_out * n_taps / (lanes * steps),
+    }
+
+
+def wave64(design: str, n_taps: int, groups: int = 4, tile: int = 4, lanes: int = 64) -> Dict[str, float]:
+    """The same model for a wavefront that streams ``groups`` register groups of
+    ``lanes`` x ``tile`` consecutive elements (the HIP kernels' layout).
+
+    FBS: every (lane, tile slot) is a PE that owns one output; the array runs
+         n_taps steps per group and every PE-step is a useful multiply-add.
+    SBM: the PE vector also carries the n_taps-1 slots the partial sums migrate
+         through, so a chunk of lanes*tile*groups inputs yields n_taps-1 fewer
+         outputs (the paper's vector length Q+CCC-1).
+    """
+    n_pe = lanes * tile * groups
+    if design == "FBS":
+        outs, steps = n_pe, n_taps
+    elif design == "SBM":
+        outs, steps = n_pe - (n_taps - 1), n_taps
+    else:
+        raise ValueError("wave64 model is written for the wave-wide designs FBS and SBM")
+    return {"lanes": n_pe, "steps": steps, "outturn": outs / steps,
+            "utilisation": outs * n_taps / (n_pe * steps)}

@@ -1,0 +1,265 @@
+"""Pins for the CPU oracle: things the paper and the mathematics fix.
+
+Each test is chosen so that one plausible mistake in the oracle (a flipped
+filter, a transposed operand, a dropped tap, a wrong extent, a pitch mix-up,
+fp32 instead of fp64 sums) fails it.  Nothing here touches the GPU path.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _parse_rows(txt):
+    rows = [[float(v) for v in row.split()] for row in txt.strip().split(";")]
+    return np.array(rows, dtype=np.float32)
+
+
+def _hand_cases():
+    cases = []
+    with open(os.path.join(GOLDEN, "hand_sums.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            kind, x, w, y = [p.strip() for p in line.split("|")]
+            if kind == "1d":
+                cases.append((kind, _parse_rows(x)[0], _parse_rows(w)[0], _parse_rows(y)[0].astype(np.float64)))
+            else:
+                cases.append((kind, _parse_rows(x), _parse_rows(w), _parse_rows(y).astype(np.float64)))
+    return cases
+
+
+@pytest.mark.parametrize("case", _hand_cases(), ids=lambda c: f"{c[0]}-{c[1].shape}-{c[2].shape}")
+def test_hand_expanded_sums(case):
+    kind, x, w, y = case
+    got = oracle.conv1d(x, w) if kind == "1d" else oracle.conv2d(x, w)
+    assert got.shape == y.shape
+    assert np.array_equal(got, y)
+
+
+# ---------------------------------------------------------------- delta filters
+@pytest.mark.parametrize("k,j", [(1, 0), (5, 0), (5, 3), (5, 4), (16, 7), (64, 63)])
+def test_delta_1d_reproduces_shifted_input(k, j):
+    rng = np.random.default_rng(7)
+    x = rng.uniform(-1, 1, 300).astype(np.float32)
+    w = np.zeros(k, np.float32)
+    w[j] = 1.0
+    y = oracle.conv1d(x, w)
+    assert np.array_equal(y, x[j:j + len(x) - k + 1].astype(np.float64))
+
+
+@pytest.mark.parametrize("kh,kw,p,q", [(3, 3, 0, 0), (3, 3, 2, 1), (5, 5, 1, 4), (11, 11, 10, 0), (2, 7, 1, 6)])
+def test_delta_2d_reproduces_shifted_image(kh, kw, p, q):
+    rng = np.random.default_rng(8)
+    x = rng.uniform(0, 1, (37, 53)).astype(np.float32)
+    f = np.zeros((kh, kw), np.float32)
+    f[p, q] = 1.0
+    y = oracle.conv2d(x, f)
+    oh, ow = 37 - kh + 1, 53 - kw + 1
+    assert np.array_equal(y, x[p:p + oh, q:q + ow].astype(np.float64))
+
+
+# ------------------------------------------------------------------- linearity
+def test_linearity_in_taps_and_signal_1d():
+    rng = np.random.default_rng(9)
+    # multiples of 2^-10 in [-1, 1]: sums and power-of-two multiples stay exact in fp32
+    grid = lambda n: (rng.integers(-1024, 1025, n) / 1024.0).astype(np.float32)
+    x1, x2 = grid(500), grid(500)
+    w1, w2 = grid(16), grid(16)
+    a, b = 0.5, -4.0
+    wc = (a * w1 + b * w2).astype(np.float32)
+    assert np.array_equal(wc.astype(np.float64), a * w1.astype(np.float64) + b * w2.astype(np.float64))
+    lhs = oracle.conv1d(x1, wc)
+    rhs = a * oracle.conv1d(x1, w1) + b * oracle.conv1d(x1, w2)
+    assert np.allclose(lhs, rhs, rtol=0, atol=1e-13)
+    xs = (x1 + x2).astype(np.float32)
+    assert np.array_equal(xs.astype(np.float64), x1.astype(np.float64) + x2.astype(np.float64))
+    assert np.allclose(oracle.conv1d(xs, w1), oracle.conv1d(x1, w1) + oracle.conv1d(x2, w1), rtol=0, atol=1e-13)
+    assert np.array_equal(oracle.conv1d((2.0 * x1).astype(np.float32), w1), 2.0 * oracle.conv1d(x1, w1))
+
+
+def test_linearity_2d():
+    rng = np.random.default_rng(10)
+    x = rng.uniform(0, 1, (40, 41)).astype(np.float32)
+    f1 = rng.integers(-4, 5, (5, 5)).astype(np.float32)
+    f2 = rng.integers(-4, 5, (5, 5)).astype(np.float32)
+    lhs = oracle.conv2d(x, 2 * f1 - 3 * f2)
+    rhs = 2 * oracle.conv2d(x, f1) - 3 * oracle.conv2d(x, f2)
+    assert np.allclose(lhs, rhs, rtol=0, atol=1e-12)
+
+
+# ------------------------------------------------------------------ separable
+def test_separable_filter_equals_two_1d_passes():
+    rng = np.random.default_rng(11)
+    # integer-valued data so both routes are exact and can be compared bit for bit
+    x = rng.integers(-9, 10, (33, 47)).astype(np.float32)
+    u = rng.integers(-3, 4, 5).astype(np.float32)      # down the rows  (index p)
+    v = rng.integers(-3, 4, 4).astype(np.float32)      # along a row    (index q)
+    f = np.outer(u, v).astype(np.float32)
+    y2 = oracle.conv2d(x, f)
+    rows = np.stack([oracle.conv1d(x[r], v) for r in range(x.shape[0])])            # (33, 44)
+    rows32 = rows.astype(np.float32)
+    assert np.array_equal(rows32.astype(np.float64), rows)
+    cols = np.stack([oracle.conv1d(rows32[:, c].copy(), u) for c in range(rows.shape[1])], axis=1)
+    assert cols.shape == y2.shape == (29, 44)
+    assert np.array_equal(cols, y2)
+
+
+def test_separable_random_floats():
+    rng = np.random.default_rng(12)
+    x = rng.uniform(0, 1, (30, 31)).astype(np.float32)
+    u = rng.uniform(-1, 1, 5).astype(np.float32)
+    v = rng.uniform(-1, 1, 5).astype(np.float32)
+    f64 = np.outer(u.astype(np.float64), v.astype(np.float64))
+    f = f64.astype(np.float32)
+    y2 = oracle.conv2d(x, f)
+    # two passes in float64 numpy (rows then columns)
+    x64 = x.astype(np.float64)
+    rows = sum(v[q].astype(np.float64) * x64[:, q:q + 27] for q in range(5))
+    both = sum(u[p].astype(np.float64) * rows[p:p + 26, :] for p in range(5))
+    # f was rounded to fp32: bound that perturbation by sum|df||x|
+    bound = np.abs(f.astype(np.float64) - f64).sum() * 1.0 + 1e-13
+    assert np.max(np.abs(y2 - both)) <= bound
+
+
+# ---------------------------------------------------------------- closed forms
+def test_constant_and_ramp_and_box_closed_forms():
+    w = np.array([0.5, -1.25, 2.0, 0.75, -3.0], np.float32)
+    n = 200
+    ones = np.ones(n, np.float32)
+    assert np.array_equal(oracle.conv1d(ones, w), np.full(n - 4, float(w.astype(np.float64).sum())))
+    ramp = np.arange(n, dtype=np.float32)
+    sw = w.astype(np.float64).sum()
+    skw = (np.arange(5) * w.astype(np.float64)).sum()
+    assert np.array_equal(oracle.conv1d(ramp, w), np.arange(n - 4) * sw + skw)
+    # box filter = difference of prefix sums (integer data: exact)
+    rng = np.random.default_rng(13)
+    x = rng.integers(-100, 101, n).astype(np.float32)
+    box = np.ones(16, np.float32)
+    pre = np.concatenate([[0.0], np.cumsum(x.astype(np.float64))])
+    assert np.array_equal(oracle.conv1d(x, box), pre[16:] - pre[:-16])
+
+
+def test_2d_constant_ramp_closed_forms():
+    f = np.array([[1, -2, 0.5], [0.25, 4, -1]], np.float32)       # 2 x 3
+    h, w = 9, 11
+    r, c = np.meshgrid(np.arange(h), np.arange(w), indexing="ij")
+    x = (10 * r + c).astype(np.float32)                             # x[r][c] = 10 r + c
+    y = oracle.conv2d(x, f)
+    f64 = f.astype(np.float64)
+    p, q = np.meshgrid(np.arange(2), np.arange(3), indexing="ij")
+    rr, cc = np.meshgrid(np.arange(h - 1), np.arange(w - 2), indexing="ij")
+    want = (10 * rr + cc) * f64.sum() + (f64 * (10 * p + q)).sum()
+    assert np.array_equal(y, want)
+
+
+# ------------------------------------------------- fp64 accumulation really used
+def test_sums_are_taken_in_fp64():
+    # 2^24 + 1 is not an fp32 number: an fp32 accumulator would lose the "+1".
+    x = np.array([16777216.0, 1.0, 1.0], np.float32)
+    w = np.array([1.0, 1.0, 1.0], np.float32)
+    assert oracle.conv1d(x, w)[0] == 16777218.0
+    x2 = np.array([[16777216.0, 1.0], [1.0, 1.0]], np.float32)
+    assert oracle.conv2d(x2, np.ones((2, 2), np.float32))[0, 0] == 16777219.0
+
+
+# -------------------------------------------------- library routines, float64
+@pytest.mark.parametrize("n,k", [(16, 16), (17, 16), (1000, 5), (257, 64), (5, 1)])
+def test_against_numpy_correlate_float64(n, k):
+    rng = np.random.default_rng(100 + n + k)
+    x = rng.uniform(-1, 1, n).astype(np.float32)
+    w = rng.uniform(-1, 1, k).astype(np.float32)
+    want = np.correlate(x.astype(np.float64), w.astype(np.float64), mode="valid")
+    got = oracle.conv1d(x, w)
+    assert got.shape == want.shape
+    assert np.allclose(got, want, rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("shape,kshape", [((20, 33), (3, 3)), ((64, 50), (5, 5)), ((31, 29), (11, 11)), ((12, 40), (1, 7)), ((40, 12), (7, 1))])
+def test_against_torch_conv2d_float64(shape, kshape):
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(200 + shape[0])
+    x = rng.uniform(0, 1, shape).astype(np.float32)
+    f = rng.uniform(-1, 1, kshape).astype(np.float32)
+    want = torch.nn.functional.conv2d(torch.from_numpy(x).double()[None, None],
+                                      torch.from_numpy(f).double()[None, None])[0, 0].numpy()
+    got = oracle.conv2d(x, f)
+    assert got.shape == want.shape
+    assert np.allclose(got, want, rtol=0, atol=1e-12)
+
+
+def test_against_torch_conv1d_float64():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(300)
+    x = rng.uniform(-1, 1, 4099).astype(np.float32)
+    w = rng.uniform(-1, 1, 16).astype(np.float32)
+    want = torch.nn.functional.conv1d(torch.from_numpy(x).double()[None, None],
+                                      torch.from_numpy(w).double()[None, None])[0, 0].numpy()
+    assert np.allclose(oracle.conv1d(x, w), want, rtol=0, atol=1e-13)
+
+
+# ----------------------------------------------------------- brute force, tiny
+def test_brute_force_python_loops_tiny():
+    rng = np.random.default_rng(14)
+    x = rng.uniform(-1, 1, (7, 9)).astype(np.float32)
+    f = rng.uniform(-1, 1, (3, 4)).astype(np.float32)
+    y = oracle.conv2d(x, f)
+    for r in range(5):
+        for c in range(6):
+            terms = [float(x[r + p, c + q]) * float(f[p, q]) for p in range(3) for q in range(4)]
+            z = 0.0
+            for t in terms:          # same order as the definition: p outer, q inner
+                z += t
+            assert y[r, c] == z
+
+
+# ----------------------------------------------------- thread count is harmless
+def test_thread_count_does_not_change_the_result():
+    rng = np.random.default_rng(15)
+    x = rng.uniform(-1, 1, 10007).astype(np.float32)
+    w = rng.uniform(-1, 1, 16).astype(np.float32)
+    assert np.array_equal(oracle.conv1d(x, w, nthreads=1), oracle.conv1d(x, w, nthreads=4))
+    img = rng.uniform(0, 1, (65, 70)).astype(np.float32)
+    f = rng.uniform(-1, 1, (5, 5)).astype(np.float32)
+    assert np.array_equal(oracle.conv2d(img, f, nthreads=1), oracle.conv2d(img, f, nthreads=3))
+
+
+# ------------------------------------------------------------- parity metric
+def test_absdot_and_metric():
+    x = np.array([1, -2, 3, -4], np.float32)
+    w = np.array([-1, 2], np.float32)
+    assert np.array_equal(oracle.absdot1d(x, w), np.array([5.0, 8.0, 11.0]))
+    img = np.array([[1, -2], [-3, 4]], np.float32)
+    assert oracle.absdot2d(img, np.array([[-1, 1], [1, -1]], np.float32))[0, 0] == 10.0
+    ref = np.array([1.0, 2.0, 0.0])
+    scale = np.array([2.0, 4.0, 0.0])
+    assert oracle.max_rel_err(ref, ref, scale) == 0.0
+    assert oracle.max_rel_err(ref + np.array([0.0, 4e-5, 0.0]), ref, scale) == pytest.approx(1e-5)
+    # a non-zero output where every product is zero can never be right
+    assert oracle.max_rel_err(ref + np.array([0.0, 0.0, 1e-30]), ref, scale) == float("inf")
+    assert oracle.max_rel_err(np.array([np.nan, 2.0, 0.0]), ref, scale) == float("inf")
+
+
+def test_bad_arguments_raise():
+    with pytest.raises(ValueError):
+        oracle.conv1d(np.ones(3, np.float32), np.ones(4, np.float32))
+    with pytest.raises(ValueError):
+        oracle.conv2d(np.ones((3, 3), np.float32), np.ones((4, 1), np.float32))
+
+
+# -------------------------------------------- planted mistakes must be caught
+def test_pins_would_catch_a_flipped_or_transposed_filter():
+    # sanity of the pins themselves: a flipped / transposed variant of the
+    # definition disagrees with the hand-expanded fixtures.
+    x = np.array([1, 2, 4, 8, 16], np.float64)
+    w = np.array([3, 0, -1], np.float64)
+    flipped = np.convolve(x, w, mode="valid")          # true convolution = flipped taps
+    assert not np.array_equal(flipped, np.array([-1.0, -2.0, -4.0]))
+    img = np.arange(1, 10, dtype=np.float32).reshape(3, 3)
+    f = np.array([[1, 2], [3, 4]], np.float32)
+    assert not np.array_equal(oracle.conv2d(img, f.T.copy()), np.array([[37.0, 47.0], [67.0, 77.0]]))
