@@ -1,0 +1,139 @@
+/*
+ * sysconv.h -- C ABI of libsysconv: 1-D and 2-D fp32 "valid" convolution run as
+ * a software systolic array inside the 64-lane wavefronts of an AMD MI355X
+ * (gfx950).
+ *
+ * The operations are the ones the paper "Systolic Computing on GPUs for
+ * Productive Performance" (arXiv 2010.15884) uses as its examples:
+ *
+ *   1-D, Eq. 2 (Section 3.1):  y[c]    = sum_q         x[c+q]      * w[q]
+ *   2-D, Eq. 3 (Section 5):    y[r][c] = sum_p sum_q   x[r+p][c+q] * f[p][q]
+ *
+ * No filter flip, no padding: n inputs and k taps give n-k+1 outputs.  The
+ * paper's systolic (fast) axis c,q is the column of a row-major image.
+ * Data and arithmetic are fp32 (the paper's SIMD8 float vectors, Section 6);
+ * the order of the k (or kh*kw) fused multiply-adds depends on the projection,
+ * so projections agree with each other to rounding, not bit for bit.
+ *
+ * A "projection" is one of the space-time mappings of Section 3.1 / Table 2,
+ * named (input, weight, partial sum) with B = broadcast, F = forwarded from
+ * PE to PE, S = stays, M = migrates, S = sediments:
+ *
+ *   FBS  partial sums and weights stay in registers, inputs move one PE per
+ *        time step (Table 2, row 3 left).  PE = output position; here four
+ *        consecutive PEs share a lane, so three of four hand-overs are
+ *        register renames and the fourth is a one-lane DPP move.
+ *   SBM  inputs stay, partial sums move one PE per step, results appear k-1
+ *        PEs further on (Section 3.1, the paper's worked example).
+ *   BFS  partial sums stay, each input is broadcast to every PE that needs
+ *        it while the weights move past (Table 2, row 2 left).  Here the PE
+ *        array runs along the per-lane registers (1-D: consecutive outputs of
+ *        one lane; 2-D: consecutive output rows of one lane).
+ *
+ * Conventions common to every entry point
+ *   - d_* pointers are DEVICE memory on the current HIP device; h_* pointers
+ *     are HOST memory.  The caller owns all of them.  The library allocates
+ *     nothing on the device and keeps no state between calls.
+ *   - Host taps are copied into the kernel-argument block before the call
+ *     returns; the caller may free or change them immediately.
+ *   - Calls are asynchronous: work is enqueued on `stream` (0 = the null
+ *     stream) and the call returns without synchronising.
+ *   - Device buffers need only 4-byte alignment; 16-byte aligned bases and
+ *     pitches that are multiples of 4 elements are fastest.
+ *   - Arguments are validated before any HIP call is made.  Nothing aborts:
+ *     every failure is an integer status and no kernel is launched.
+ *   - Input and output ranges must not overlap (SYS_ERR_ALIAS).
+ */
+#ifndef SYSCONV_H
+#define SYSCONV_H
+
+#include <stddef.h>
+
+#ifdef SYSCONV_NO_HIP_HEADER
+typedef struct ihipStream_t *hipStream_t;
+#else
+#include <hip/hip_runtime_api.h>
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SYS_OK = 0,
+    SYS_ERR_NULL = 1,         /* a required pointer is NULL                          */
+    SYS_ERR_SIZE = 2,         /* k < 1, k > n, pitch < width, empty output, ...      */
+    SYS_ERR_ALIAS = 3,        /* input and output byte ranges overlap                */
+    SYS_ERR_UNSUPPORTED = 4,  /* size beyond the limits below / unknown projection /
+                                 projection not built for this filter size          */
+    SYS_ERR_HIP = 5           /* a HIP call failed; see sys_last_hip_error()         */
+} sys_status_t;
+
+typedef enum {
+    SYS_PROJ_AUTO = 0,        /* the fastest projection available for the size       */
+    SYS_PROJ_FBS = 1,
+    SYS_PROJ_BFS = 2,
+    SYS_PROJ_SBM = 3
+} sys_projection_t;
+
+/* Limits.  Larger filters return SYS_ERR_UNSUPPORTED. */
+#define SYS_MAX_K1D 64        /* taps of a 1-D filter                                */
+#define SYS_MAX_K2D 15        /* rows and columns of a 2-D filter                    */
+
+/*
+ * 1-D valid convolution, Eq. 2:  d_y[c] = sum_{q<k} d_x[c+q] * h_w[q],  c < n-k+1.
+ *   d_x   device, n floats (read only)
+ *   h_w   host, k floats, 1 <= k <= min(n, SYS_MAX_K1D)
+ *   d_y   device, n-k+1 floats (written; nothing else is touched)
+ *   projection  a sys_projection_t; AUTO, FBS and SBM accept every k in range;
+ *         sys_conv1d_has tells whether BFS is built for a given k
+ */
+int sys_conv1d(const float *d_x, size_t n,
+               const float *h_w, int k,
+               float *d_y,
+               int projection, hipStream_t stream);
+
+/*
+ * 2-D valid convolution, Eq. 3, single channel, row-major:
+ *   d_y[r*y_pitch + c] = sum_{p<kh} sum_{q<kw} d_x[(r+p)*x_pitch + c+q] * h_f[p*kw+q]
+ * for r < h-kh+1, c < w-kw+1.
+ *   d_x      device, h rows of w floats, row stride x_pitch elements (>= w)
+ *   h_f      host, kh*kw floats row-major, 1 <= kh <= min(h, SYS_MAX_K2D), same for kw / w
+ *   d_y      device, h-kh+1 rows of w-kw+1 floats, row stride y_pitch elements
+ *            (>= w-kw+1); elements between rows are left untouched
+ *   projection  FBS accepts every filter in range; BFS and SBM are built for a
+ *            fixed list of filter sizes (sys_conv2d_has) and return
+ *            SYS_ERR_UNSUPPORTED otherwise; AUTO never does.
+ */
+int sys_conv2d(const float *d_x, int h, int w, size_t x_pitch,
+               const float *h_f, int kh, int kw,
+               float *d_y, size_t y_pitch,
+               int projection, hipStream_t stream);
+
+/* 1 if sys_conv1d(projection) is built for a k-tap filter, else 0. */
+int sys_conv1d_has(int projection, int k);
+
+/* 1 if sys_conv2d(projection) is built for a kh x kw filter, else 0. */
+int sys_conv2d_has(int projection, int kh, int kw);
+
+/*
+ * Plain device-to-device copy of n floats with 16-byte accesses.  It is the
+ * yard-stick the benchmark prints beside every convolution ("what the memory
+ * system gives a streaming kernel of this footprint") and the kernel of known
+ * traffic that hardware byte counters are calibrated against.
+ */
+int sys_copy_f32(const float *d_src, float *d_dst, size_t n, hipStream_t stream);
+
+const char *sys_status_string(int status);
+const char *sys_projection_name(int projection);
+
+/* hipError_t (as int) behind the calling thread's last SYS_ERR_HIP; 0 if none. */
+int sys_last_hip_error(void);
+
+/* major*10000 + minor*100 + patch */
+int sys_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SYSCONV_H */

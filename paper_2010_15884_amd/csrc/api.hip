@@ -1,0 +1,150 @@
+// C-ABI layer of libsysconv: argument validation, projection dispatch, status
+// reporting.  Every check runs before the first HIP call, so the error paths
+// work on a host without a GPU.
+#include "sysconv.h"
+
+#include "launch.h"
+
+#include <stdint.h>
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return SYS_OK;
+    g_last_hip_error = (int)e;
+    return SYS_ERR_HIP;
+}
+
+bool ranges_overlap(const void* a, size_t a_bytes, const void* b, size_t b_bytes)
+{
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + b_bytes && b0 < a0 + a_bytes;
+}
+
+bool known_projection(int p)
+{
+    return p == SYS_PROJ_AUTO || p == SYS_PROJ_FBS || p == SYS_PROJ_BFS || p == SYS_PROJ_SBM;
+}
+
+bool misaligned(const void* p) { return ((uintptr_t)p & 3u) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+int sys_conv1d(const float* d_x, size_t n, const float* h_w, int k, float* d_y, int projection,
+               hipStream_t stream)
+{
+    if (!d_x || !h_w || !d_y) return SYS_ERR_NULL;
+    if (k < 1 || (size_t)k > n) return SYS_ERR_SIZE;
+    if (!known_projection(projection) || k > SYS_MAX_K1D) return SYS_ERR_UNSUPPORTED;
+    if (misaligned(d_x) || misaligned(d_y)) return SYS_ERR_UNSUPPORTED;
+    if (n > ((size_t)1 << 40)) return SYS_ERR_UNSUPPORTED;
+    const size_t m = n - (size_t)k + 1;
+    if (ranges_overlap(d_x, n * sizeof(float), d_y, m * sizeof(float))) return SYS_ERR_ALIAS;
+
+    switch (projection) {
+    case SYS_PROJ_AUTO:
+    case SYS_PROJ_FBS: return hip_status(sysconv::launch_conv1d_fbs(d_x, n, h_w, k, d_y, stream));
+    case SYS_PROJ_SBM: return hip_status(sysconv::launch_conv1d_sbm(d_x, n, h_w, k, d_y, stream));
+    case SYS_PROJ_BFS:
+        if (!sysconv::has_conv1d_bfs(k)) return SYS_ERR_UNSUPPORTED;
+        return hip_status(sysconv::launch_conv1d_bfs(d_x, n, h_w, k, d_y, stream));
+    default: return SYS_ERR_UNSUPPORTED;
+    }
+}
+
+int sys_conv1d_has(int projection, int k)
+{
+    if (k < 1 || k > SYS_MAX_K1D) return 0;
+    switch (projection) {
+    case SYS_PROJ_AUTO:
+    case SYS_PROJ_FBS:
+    case SYS_PROJ_SBM: return 1;
+    case SYS_PROJ_BFS: return sysconv::has_conv1d_bfs(k) ? 1 : 0;
+    default: return 0;
+    }
+}
+
+int sys_conv2d_has(int projection, int kh, int kw)
+{
+    if (kh < 1 || kw < 1 || kh > SYS_MAX_K2D || kw > SYS_MAX_K2D) return 0;
+    switch (projection) {
+    case SYS_PROJ_AUTO:
+    case SYS_PROJ_FBS: return 1;
+    case SYS_PROJ_BFS: return sysconv::has_conv2d_bfs(kh, kw) ? 1 : 0;
+    case SYS_PROJ_SBM: return sysconv::has_conv2d_sbm(kh, kw) ? 1 : 0;
+    default: return 0;
+    }
+}
+
+int sys_conv2d(const float* d_x, int h, int w, size_t x_pitch, const float* h_f, int kh, int kw, float* d_y,
+               size_t y_pitch, int projection, hipStream_t stream)
+{
+    if (!d_x || !h_f || !d_y) return SYS_ERR_NULL;
+    if (h < 1 || w < 1 || kh < 1 || kw < 1 || kh > h || kw > w) return SYS_ERR_SIZE;
+    const int oh = h - kh + 1, ow = w - kw + 1;
+    if (x_pitch < (size_t)w || y_pitch < (size_t)ow) return SYS_ERR_SIZE;
+    if (!known_projection(projection) || kh > SYS_MAX_K2D || kw > SYS_MAX_K2D) return SYS_ERR_UNSUPPORTED;
+    if (misaligned(d_x) || misaligned(d_y)) return SYS_ERR_UNSUPPORTED;
+    if (x_pitch > ((size_t)1 << 31) || y_pitch > ((size_t)1 << 31)) return SYS_ERR_UNSUPPORTED;
+    const size_t x_bytes = ((size_t)(h - 1) * x_pitch + (size_t)w) * sizeof(float);
+    const size_t y_bytes = ((size_t)(oh - 1) * y_pitch + (size_t)ow) * sizeof(float);
+    if (ranges_overlap(d_x, x_bytes, d_y, y_bytes)) return SYS_ERR_ALIAS;
+
+    int proj = projection;
+    if (proj == SYS_PROJ_AUTO) proj = sysconv::has_conv2d_bfs(kh, kw) ? SYS_PROJ_BFS : SYS_PROJ_FBS;
+    switch (proj) {
+    case SYS_PROJ_FBS:
+        return hip_status(sysconv::launch_conv2d_fbs(d_x, h, w, x_pitch, h_f, kh, kw, d_y, y_pitch, stream));
+    case SYS_PROJ_BFS:
+        if (!sysconv::has_conv2d_bfs(kh, kw)) return SYS_ERR_UNSUPPORTED;
+        return hip_status(sysconv::launch_conv2d_bfs(d_x, h, w, x_pitch, h_f, kh, kw, d_y, y_pitch, stream));
+    case SYS_PROJ_SBM:
+        if (!sysconv::has_conv2d_sbm(kh, kw)) return SYS_ERR_UNSUPPORTED;
+        return hip_status(sysconv::launch_conv2d_sbm(d_x, h, w, x_pitch, h_f, kh, kw, d_y, y_pitch, stream));
+    default: return SYS_ERR_UNSUPPORTED;
+    }
+}
+
+int sys_copy_f32(const float* d_src, float* d_dst, size_t n, hipStream_t stream)
+{
+    if (!d_src || !d_dst) return SYS_ERR_NULL;
+    if (n < 1) return SYS_ERR_SIZE;
+    if (misaligned(d_src) || misaligned(d_dst)) return SYS_ERR_UNSUPPORTED;
+    if (ranges_overlap(d_src, n * sizeof(float), d_dst, n * sizeof(float))) return SYS_ERR_ALIAS;
+    return hip_status(sysconv::launch_copy_f32(d_src, d_dst, n, stream));
+}
+
+const char* sys_status_string(int status)
+{
+    switch (status) {
+    case SYS_OK: return "ok";
+    case SYS_ERR_NULL: return "null pointer argument";
+    case SYS_ERR_SIZE: return "invalid size (need 1 <= taps <= extent, pitch >= width)";
+    case SYS_ERR_ALIAS: return "input and output ranges overlap";
+    case SYS_ERR_UNSUPPORTED: return "unsupported size, alignment or projection";
+    case SYS_ERR_HIP: return "HIP runtime error (see sys_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+const char* sys_projection_name(int projection)
+{
+    switch (projection) {
+    case SYS_PROJ_AUTO: return "AUTO";
+    case SYS_PROJ_FBS: return "FBS";
+    case SYS_PROJ_BFS: return "BFS";
+    case SYS_PROJ_SBM: return "SBM";
+    default: return "?";
+    }
+}
+
+int sys_last_hip_error(void) { return g_last_hip_error; }
+
+int sys_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,303 @@
+// 2-D valid convolution  y[r][c] = sum_p sum_q x[r+p][c+q] * f[p][q]  (paper
+// Eq. 3; the paper's systolic axis c,q is the image column) as software
+// systolic arrays.  A wavefront always works on a strip of 256 consecutive
+// input columns held four per lane; neighbouring strips overlap by
+// 4*halo_lanes(kw) columns and the PEs whose taps reach past the strip compute
+// values that are never stored.
+#include "launch.h"
+#include "systolic.h"
+
+#include <cstdlib>
+
+namespace sysconv {
+namespace {
+
+constexpr int kXcds = 8;       // L2 caches (one per XCD); workgroups are dealt to them round-robin
+
+// Workgroup b runs on XCD b % 8.  Give every XCD one contiguous run of work
+// items, so that items that share halo rows meet in the same L2.
+__device__ __forceinline__ int xcd_contiguous(int b, int per_xcd)
+{
+    return (b % kXcds) * per_xcd + (b / kXcds);
+}
+
+// ------------------------------------------------------------- FBS 2-D -----
+// Section 6.2: "FBS ... converts a 2-D convolution into multiple FBS 1-D
+// convolutions".  A workgroup stages a (32 + kh - 1) x 256 input tile in LDS
+// once; each of its four wavefronts then owns eight output rows (eight
+// independent partial-sum vectors) and, for every filter row p, re-reads the
+// input rows r+p from LDS and runs the 1-D FBS time loop over q on them.
+// Filter sizes are run-time values.
+constexpr int kFbsRowsPerWave = 8;
+constexpr int kFbsTileRows = kFbsRowsPerWave * (kBlock / kWave);          // 32 output rows per workgroup
+constexpr int kStrip = kWave * kTile;                                      // 256 input columns
+
+template <int NT, bool MORE>
+__device__ __forceinline__ void fbs_rows(float (&e)[kFbsRowsPerWave][4], float (&acc)[kFbsRowsPerWave][4],
+                                         const float (&w)[4])
+{
+#pragma unroll
+    for (int j = 0; j < kFbsRowsPerWave; ++j) fbs_steps<NT, MORE>(e[j], acc[j], w);
+}
+
+__global__ __launch_bounds__(kBlock) void conv2d_fbs_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                            int h, int w_img, long long xp, int oh, int ow,
+                                                            long long yp, int kh, int kw, int tiles_y, int n_tiles,
+                                                            int per_xcd, Taps2D taps)
+{
+    extern __shared__ __attribute__((aligned(16))) float tile[];           // (kFbsTileRows + kh - 1) x kStrip
+
+    const int t = xcd_contiguous(blockIdx.x, per_xcd);
+    if (t >= n_tiles) return;                                              // whole workgroup leaves together
+    const int tile_y = t % tiles_y, tile_x = t / tiles_y;                  // consecutive items go down a strip
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = wave_in_block();
+    const int valid_lanes = kWave - halo_lanes(kw);
+    const int col0 = tile_x * kTile * valid_lanes;
+    const int row0 = tile_y * kFbsTileRows;
+
+    // stage: wavefront v copies input rows v, v+4, ... of the tile (1 KB each, coalesced)
+    const int in_rows = min(kFbsTileRows + kh - 1, h - row0);
+    for (int rr = wave; rr < in_rows; rr += kBlock / kWave) {
+        float v[4];
+        load4_guarded(x + (long long)(row0 + rr) * xp, col0 + kTile * lane, w_img, v);
+        f4 t4;
+        t4.x = v[0]; t4.y = v[1]; t4.z = v[2]; t4.w = v[3];
+        *reinterpret_cast<f4*>(tile + rr * kStrip + kTile * lane) = t4;
+    }
+    __syncthreads();
+
+    float acc[kFbsRowsPerWave][4];
+#pragma unroll
+    for (int j = 0; j < kFbsRowsPerWave; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[j][i] = 0.0f;
+
+    const int lrow0 = wave * kFbsRowsPerWave;
+#pragma nounroll
+    for (int p = 0; p < kh; ++p) {
+        float e[kFbsRowsPerWave][4];
+#pragma unroll
+        for (int j = 0; j < kFbsRowsPerWave; ++j) {
+            // rows below the staged part of the tile hold stale LDS; they only feed
+            // output rows >= oh, which are not stored
+            const f4 t4 = *reinterpret_cast<const f4*>(tile + (lrow0 + j + p) * kStrip + kTile * lane);
+            e[j][0] = t4.x; e[j][1] = t4.y; e[j][2] = t4.z; e[j][3] = t4.w;
+        }
+        const float* fp = taps.f + p * kw;
+        int q = 0;
+#pragma nounroll
+        for (; q + 4 < kw; q += 4) {
+            const float w[4] = {fp[q], fp[q + 1], fp[q + 2], fp[q + 3]};
+            fbs_rows<4, true>(e, acc, w);
+        }
+        const float w[4] = {fp[q], fp[q + 1], fp[q + 2], fp[q + 3]};
+        switch (kw - q) {
+        case 4: fbs_rows<4, false>(e, acc, w); break;
+        case 3: fbs_rows<3, false>(e, acc, w); break;
+        case 2: fbs_rows<2, false>(e, acc, w); break;
+        default: fbs_rows<1, false>(e, acc, w); break;
+        }
+    }
+
+    if (lane < valid_lanes) {
+#pragma unroll
+        for (int j = 0; j < kFbsRowsPerWave; ++j) {
+            const int r = row0 + lrow0 + j;
+            if (r < oh) store4_guarded(y + (long long)r * yp, col0 + kTile * lane, ow, acc[j]);
+        }
+    }
+}
+
+// A zero the optimiser cannot see through (one SALU move).
+__device__ __forceinline__ int opaque_zero()
+{
+    int z;
+    asm volatile("s_mov_b32 %0, 0" : "=s"(z));
+    return z;
+}
+
+// ------------------------------------------------------------- BFS 2-D -----
+// Along the rows the array is the BFS design of Table 2 (row 2 left) with
+// (c, q) read as (r, p): PE = output row, time = input row rho = r + p.  The
+// PEs are the KH live partial-sum vectors of a lane; at step rho the input row
+// rho is broadcast to all of them, PE r applies filter row p = rho - r (the
+// weights move one PE per step while the partial sums stay), and the PE whose
+// last filter row was just applied retires its output row.  Along a row the
+// KW-wide window of every PE is built once by KW-1 FBS hand-overs and reused
+// by all KH filter rows, so lane traffic is amortised KH times.  Everything
+// streams from global memory through registers: no LDS.
+//
+// A wavefront walks `rows` output rows of one strip; PD input rows are in
+// flight ahead of the one being consumed.
+template <int KH, int KW, int PD>
+__global__ __launch_bounds__(kBlock) void conv2d_bfs_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                            int w_img, long long xp, int oh, int ow,
+                                                            long long yp, int rows, int row_blocks, int n_items,
+                                                            int per_xcd, Taps2D taps)
+{
+    constexpr bool kReloadTaps = KH * KW > 25;
+    const int item = xcd_contiguous(blockIdx.x, per_xcd) * (kBlock / kWave) + wave_in_block();
+    if (item >= n_items) return;                                           // uniform per wavefront
+    const int rb = item % row_blocks, strip = item / row_blocks;           // consecutive items go down a strip
+    const int lane = threadIdx.x & (kWave - 1);
+    constexpr int valid_lanes = kWave - halo_lanes(KW);
+    const int col = strip * kTile * valid_lanes + kTile * lane;
+    const int r0 = rb * rows;
+    const int rows_out = min(rows, oh - r0);
+    const int rows_in = rows_out + KH - 1;
+    const float* xrow = x + (long long)r0 * xp;
+
+    float ring[PD][4];
+#pragma unroll
+    for (int d = 0; d < PD; ++d) {
+        if (d < rows_in) load4_guarded(xrow + (long long)d * xp, col, w_img, ring[d]);
+        else ring[d][0] = ring[d][1] = ring[d][2] = ring[d][3] = 0.0f;
+    }
+
+    float acc[KH][4];
+#pragma unroll
+    for (int s = 0; s < KH; ++s) acc[s][0] = acc[s][1] = acc[s][2] = acc[s][3] = 0.0f;
+
+    for (int rho0 = 0; rho0 < rows_in; rho0 += KH) {
+#pragma unroll
+        for (int ph = 0; ph < KH; ++ph) {
+            const int rho = rho0 + ph;
+            if (rho >= rows_in) break;
+
+            // window of input row rho: win[m] = x[rho][col + m], m < KW + 3
+            float win[KW + 3];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) win[i] = ring[0][i];
+#pragma unroll
+            for (int d = 0; d + 1 < PD; ++d)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ring[d][i] = ring[d + 1][i];
+            if (rho + PD < rows_in) load4_guarded(xrow + (long long)(rho + PD) * xp, col, w_img, ring[PD - 1]);
+#pragma unroll
+            for (int m = 4; m < KW + 3; ++m) win[m] = from_lane_above(win[m - 4]);
+
+            // broadcast the row to the KH partial-sum vectors it feeds
+#pragma unroll
+            for (int p = 0; p < KH; ++p) {
+                const int slot = (ph - p + KH) % KH;                       // compile-time after unrolling
+                const int r = rho - p;
+                if (r >= 0 && r < rows_out) {
+                    // Small filters keep all taps in SGPRs for the whole kernel.  Larger
+                    // ones would spill them, so each filter row is re-fetched here with
+                    // scalar loads; the offset is made opaque to keep the loads in the loop.
+                    const float* fp = taps.f + p * KW + (kReloadTaps ? opaque_zero() : 0);
+#pragma unroll
+                    for (int q = 0; q < KW; ++q) {
+                        const float wv = fp[q];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[slot][i] = __builtin_fmaf(wv, win[q + i], acc[slot][i]);
+                    }
+                }
+            }
+
+            // output row rho-(KH-1) has now seen all its filter rows
+            const int done = rho - (KH - 1);
+            const int dslot = (ph + 1) % KH;
+            if (done >= 0 && lane < valid_lanes)
+                store4_guarded(y + (long long)(r0 + done) * yp, col, ow, acc[dslot]);
+            acc[dslot][0] = acc[dslot][1] = acc[dslot][2] = acc[dslot][3] = 0.0f;
+        }
+    }
+}
+
+int env_int(const char* name, int fallback)
+{
+    const char* v = std::getenv(name);
+    if (!v || !*v) return fallback;
+    const int x = std::atoi(v);
+    return x > 0 ? x : fallback;
+}
+
+void fill_taps(Taps2D& taps, const float* f, int n)
+{
+    for (int i = 0; i < kMaxK2D * kMaxK2D + 7; ++i) taps.f[i] = i < n ? f[i] : 0.0f;
+}
+
+template <int KH, int KW, int PD>
+hipError_t launch_bfs(const float* x, int h, int w, size_t xp, const float* f, float* y, size_t yp, hipStream_t s)
+{
+    Taps2D taps;
+    fill_taps(taps, f, KH * KW);
+    const int oh = h - KH + 1, ow = w - KW + 1;
+    constexpr int valid_lanes = kWave - halo_lanes(KW);
+    const int strips = (ow + kTile * valid_lanes - 1) / (kTile * valid_lanes);
+    // rows per wavefront: enough wavefronts to fill 256 CUs several times over,
+    // but tall enough that the KH-1 halo rows stay a small part of the reads
+    static const int rows_env = env_int("SYSCONV_BFS_ROWS", 0);
+    int rows = rows_env;
+    if (rows <= 0) {
+        const int want_waves = 8192;
+        const int want_blocks = (want_waves + strips - 1) / strips;
+        rows = (oh + want_blocks - 1) / want_blocks;
+        const int min_rows = 4 * KH > 16 ? 4 * KH : 16;
+        if (rows < min_rows) rows = min_rows;
+    }
+    if (rows > oh) rows = oh;
+    const int row_blocks = (oh + rows - 1) / rows;
+    const long long n_items = (long long)row_blocks * strips;
+    const long long groups = (n_items + (kBlock / kWave) - 1) / (kBlock / kWave);
+    const long long per_xcd = (groups + kXcds - 1) / kXcds;
+    const long long blocks = per_xcd * kXcds;
+    if (blocks > 0x7fffffffLL || n_items > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((conv2d_bfs_kernel<KH, KW, PD>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
+                       x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, (int)n_items,
+                       (int)per_xcd, taps);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_conv2d_fbs(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
+                             float* y, size_t yp, hipStream_t s)
+{
+    Taps2D taps;
+    fill_taps(taps, f, kh * kw);
+    const int oh = h - kh + 1, ow = w - kw + 1;
+    const int cols = kTile * (kWave - halo_lanes(kw));
+    const int tiles_x = (ow + cols - 1) / cols;
+    const int tiles_y = (oh + kFbsTileRows - 1) / kFbsTileRows;
+    const long long n_tiles = (long long)tiles_x * tiles_y;
+    const long long per_xcd = (n_tiles + kXcds - 1) / kXcds;
+    const long long blocks = per_xcd * kXcds;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const size_t lds = (size_t)(kFbsTileRows + kh - 1) * kStrip * sizeof(float);
+    hipLaunchKernelGGL(conv2d_fbs_kernel, dim3((unsigned)blocks), dim3(kBlock), lds, s,
+                       x, y, h, w, (long long)xp, oh, ow, (long long)yp, kh, kw, tiles_y, (int)n_tiles,
+                       (int)per_xcd, taps);
+    return hipGetLastError();
+}
+
+bool has_conv2d_bfs(int kh, int kw)
+{
+    return (kh == kw) && (kh == 2 || kh == 3 || kh == 5 || kh == 7 || kh == 9 || kh == 11);
+}
+
+hipError_t launch_conv2d_bfs(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
+                             float* y, size_t yp, hipStream_t s)
+{
+    if (kh != kw) return hipErrorInvalidValue;
+    switch (kh) {
+    case 2: return launch_bfs<2, 2, 4>(x, h, w, xp, f, y, yp, s);
+    case 3: return launch_bfs<3, 3, 4>(x, h, w, xp, f, y, yp, s);
+    case 5: return launch_bfs<5, 5, 3>(x, h, w, xp, f, y, yp, s);
+    case 7: return launch_bfs<7, 7, 2>(x, h, w, xp, f, y, yp, s);
+    case 9: return launch_bfs<9, 9, 2>(x, h, w, xp, f, y, yp, s);
+    case 11: return launch_bfs<11, 11, 2>(x, h, w, xp, f, y, yp, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+bool has_conv2d_sbm(int, int) { return false; }
+
+hipError_t launch_conv2d_sbm(const float*, int, int, size_t, const float*, int, int, float*, size_t, hipStream_t)
+{
+    return hipErrorNotSupported;
+}
+
+}  // namespace sysconv

@@ -1,0 +1,116 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before any HIP call."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2010_15884_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FP = ctypes.POINTER(ctypes.c_float)
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "sysconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sys_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_strings_and_version():
+    assert B.sys_version() >= 100
+    assert B.status_string(B.SYS_OK) == "ok"
+    for s in range(1, 6):
+        assert B.status_string(s) not in ("ok", "unknown status")
+    assert B.status_string(99) == "unknown status"
+    assert [B.projection_name(p) for p in range(4)] == ["AUTO", "FBS", "BFS", "SBM"]
+    assert B.projection_name(17) == "?"
+
+
+def _w(k):
+    w = np.ones(max(k, 1), np.float32)
+    return w, w.ctypes.data_as(FP)
+
+
+# fake, 4-byte aligned, non-overlapping "device" addresses: validation never dereferences them
+X, Y = 0x10000000, 0x40000000
+
+
+@pytest.mark.parametrize("args,want", [
+    ((None, 100, "w", 5, Y, 1), B.SYS_ERR_NULL),
+    ((X, 100, None, 5, Y, 1), B.SYS_ERR_NULL),
+    ((X, 100, "w", 5, None, 1), B.SYS_ERR_NULL),
+    ((X, 100, "w", 0, Y, 1), B.SYS_ERR_SIZE),
+    ((X, 100, "w", -3, Y, 1), B.SYS_ERR_SIZE),
+    ((X, 4, "w", 5, Y, 1), B.SYS_ERR_SIZE),
+    ((X, 0, "w", 1, Y, 1), B.SYS_ERR_SIZE),
+    ((X, 100, "w", 65, Y, 1), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, "w", 5, Y, 7), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, "w", 5, Y, -1), B.SYS_ERR_UNSUPPORTED),
+    ((X + 2, 100, "w", 5, Y, 1), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, "w", 5, X, 1), B.SYS_ERR_ALIAS),
+    ((X, 100, "w", 5, X + 4 * 99, 1), B.SYS_ERR_ALIAS),
+    ((X + 4 * 95, 100, "w", 5, X, 1), B.SYS_ERR_ALIAS),
+])
+def test_conv1d_validation(args, want):
+    x, n, w, k, y, proj = args
+    keep, wp = _w(k)
+    got = B.lib().sys_conv1d(x, n, wp if w else None, k, y, proj, None)
+    assert got == want, B.status_string(got)
+
+
+@pytest.mark.parametrize("args,want", [
+    ((None, 10, 10, 10, "f", 3, 3, Y, 8, 1), B.SYS_ERR_NULL),
+    ((X, 10, 10, 10, None, 3, 3, Y, 8, 1), B.SYS_ERR_NULL),
+    ((X, 10, 10, 10, "f", 3, 3, None, 8, 1), B.SYS_ERR_NULL),
+    ((X, 10, 10, 10, "f", 0, 3, Y, 8, 1), B.SYS_ERR_SIZE),
+    ((X, 10, 10, 10, "f", 11, 3, Y, 8, 1), B.SYS_ERR_SIZE),
+    ((X, 10, 10, 10, "f", 3, 11, Y, 8, 1), B.SYS_ERR_SIZE),
+    ((X, 10, 10, 9, "f", 3, 3, Y, 8, 1), B.SYS_ERR_SIZE),
+    ((X, 10, 10, 10, "f", 3, 3, Y, 7, 1), B.SYS_ERR_SIZE),
+    ((X, 0, 10, 10, "f", 1, 1, Y, 10, 1), B.SYS_ERR_SIZE),
+    ((X, 100, 100, 100, "f", 16, 3, Y, 98, 1), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, 100, 100, "f", 3, 16, Y, 98, 1), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, 100, 100, "f", 3, 3, Y, 98, 9), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, 100, 100, "f", 4, 3, Y, 98, B.SYS_PROJ_BFS), B.SYS_ERR_UNSUPPORTED),
+    ((X + 1, 100, 100, 100, "f", 3, 3, Y, 98, 1), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, 100, 100, "f", 3, 3, X + 4 * 5000, 98, 1), B.SYS_ERR_ALIAS),
+])
+def test_conv2d_validation(args, want):
+    x, h, w, xp, f, kh, kw, y, yp, proj = args
+    keep = np.ones(256, np.float32)
+    got = B.lib().sys_conv2d(x, h, w, xp, keep.ctypes.data_as(FP) if f else None, kh, kw, y, yp, proj, None)
+    assert got == want, B.status_string(got)
+
+
+def test_copy_validation():
+    L = B.lib()
+    assert L.sys_copy_f32(None, Y, 10, None) == B.SYS_ERR_NULL
+    assert L.sys_copy_f32(X, None, 10, None) == B.SYS_ERR_NULL
+    assert L.sys_copy_f32(X, Y, 0, None) == B.SYS_ERR_SIZE
+    assert L.sys_copy_f32(X, X + 8, 10, None) == B.SYS_ERR_ALIAS
+    assert L.sys_copy_f32(X + 1, Y, 10, None) == B.SYS_ERR_UNSUPPORTED
+
+
+def test_conv2d_has():
+    assert B.sys_conv2d_has("FBS", 15, 15) and B.sys_conv2d_has("AUTO", 1, 9)
+    assert not B.sys_conv2d_has("FBS", 16, 3)
+    assert B.sys_conv2d_has("BFS", 3, 3) and B.sys_conv2d_has("BFS", 5, 5) and B.sys_conv2d_has("BFS", 11, 11)
+    assert not B.sys_conv2d_has("BFS", 4, 5)
+    assert not B.sys_conv2d_has(42, 3, 3)
+
+
+def test_binding_rejects_host_tensors():
+    torch = pytest.importorskip("torch")
+    with pytest.raises(TypeError):
+        B.sys_conv1d(torch.zeros(10), np.ones(3, np.float32))
