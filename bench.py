@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of libsysconv on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extras] [--no-cpu]
+
+A step is one pass of the hot path -- weight residency, input load, systolic time
+loop, output store -- over the large 1-D workload (n = 2^26 fp32 inputs, 16
+taps), launched through the C ABI with inputs already resident in HBM.  The
+single JSON line printed at the end carries
+
+  value        algorithmic GB/s of that step (4 B per input + 4 B per output + taps,
+               divided by wall time between two device synchronisations)
+  roofline     the same bytes over the kernel's own average duration (HIP events
+               recorded around every launch of the timed region, on the launch
+               stream), against the 8 TB/s HBM peak; `traffic` is the HBM byte
+               count of one launch from hardware counters when a calibrated
+               reading is stored in profiles/, else null
+  cpu_baseline the CPU oracle (plain C, fp64) timed here on the host cores
+  also         the other four workloads and every projection built for them,
+               each with GB/s, Gtap/s and its fraction of the HBM and fp32-FMA
+               peaks, and a plain dwordx4 copy of the same footprint
+
+Paper context (not a target, not comparable): on an Intel GEN9.5 iGPU the paper's
+best software-systolic designs ran up to 59 % faster than that GPU's hardware
+samplers; it reports no absolute throughput.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+FMA_PEAK_G = 39321.6             # 256 CUs x 64 lanes x 2.4 GHz, one v_fmac_f32 per lane-clock (= 78.6 TFLOP/s)
+HEADLINE = "conv1d_64m_k16"
+MALL_BYTES = 256 << 20           # last-level cache in front of HBM: rotate buffers past it
+
+
+def _parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--projection", default="AUTO")
+    ap.add_argument("--no-extras", action="store_true", help="skip the other workloads / projections")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    return ap.parse_args()
+
+
+def _stored_traffic(kernel_key: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by
+    the copy kernel's reading); kept as `traffic_bytes <key> <bytes>` lines in profiles/."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        m = re.match(r"traffic_bytes\s+(\S+)\s+(\d+)", line.strip())
+        if m and m.group(1) == kernel_key:
+            return int(m.group(2))
+    return None
+
+
+def main() -> int:
+    args = _parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2010_15884_amd import binding as B
+    from paper_2010_15884_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    B.lib()                                       # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    def rotation(wl):
+        per_pass = wl.algorithmic_bytes
+        return max(2, min(6, -(-2 * MALL_BYTES // per_pass)))
+
+    def make_launcher(wl, proj, x_host, taps):
+        nrot = rotation(wl)
+        dxs = [torch.from_numpy(x_host).cuda() for _ in range(nrot)]
+        dys = [torch.empty(wl.y_shape, dtype=torch.float32, device="cuda") for _ in range(nrot)]
+        state = {"i": 0}
+        conv = B.sys_conv1d if wl.ndim == 1 else B.sys_conv2d
+
+        def launch():
+            i = state["i"] = (state["i"] + 1) % nrot
+            conv(dxs[i], taps, dys[i], projection=proj)
+        return launch, (dxs, dys)
+
+    def time_launches(launch, steps, warmup):
+        """(wall seconds for `steps` launches, mean per-launch seconds from HIP events)."""
+        for _ in range(warmup):
+            launch()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for a, b in evs:
+            a.record(stream)
+            launch()
+            b.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        per = [a.elapsed_time(b) * 1e-3 for a, b in evs]
+        return wall, sum(per) / len(per), sorted(per)[len(per) // 2]
+
+    # ------------------------------------------------------------ headline step
+    wl = W.WORKLOADS[HEADLINE]
+    x_host, taps = W.make(wl)
+    launch, keep = make_launcher(wl, args.projection, x_host, taps)
+    wall, kern_mean, kern_med = time_launches(launch, args.steps, args.warmup)
+    ms_per_step = 1e3 * wall / args.steps
+    value = wl.algorithmic_bytes / (wall / args.steps) / 1e9
+    achieved = wl.algorithmic_bytes / kern_mean / 1e9
+    del keep, launch
+    torch.cuda.empty_cache()
+
+    result = {
+        "metric": "conv GB/s (algorithmic bytes / time), 1-D valid convolution n=2^26 K=16 fp32",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic (seeded uniform fp32, see paper_2010_15884_amd/workloads.py)",
+        "config": {"workload": HEADLINE, "n": wl.x_shape[0], "taps": wl.k_shape[0],
+                   "projection": args.projection, "algorithmic_bytes": wl.algorithmic_bytes,
+                   "gtap_per_s": round(wl.n_taps / (wall / args.steps) / 1e9, 1)},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": _stored_traffic("conv1d_fbs_k16_n64m"),
+                     "kernel": "conv1d_fbs_kernel<16>", "kernel_us_mean": round(kern_mean * 1e6, 2),
+                     "kernel_us_median": round(kern_med * 1e6, 2)},
+        "paper_context": "Intel GEN9.5, fp32: best software-systolic designs up to 59% faster than that GPU's "
+                         "hardware samplers (relative figure only; not a target)",
+    }
+
+    # ----------------------------------------------------- the other workloads
+    if not args.no_extras:
+        also = []
+        for name in W.ORDER:
+            w2 = W.WORKLOADS[name]
+            xh, tp = W.make(w2)
+            steps = 30 if w2.n_taps < 5_000_000_000 else 10
+            # plain copy of the same footprint (half read, half written)
+            n_copy = max(1, w2.algorithmic_bytes // 8)
+            nrot = rotation(w2)
+            srcs = [torch.empty(n_copy, dtype=torch.float32, device="cuda").normal_() for _ in range(nrot)]
+            dsts = [torch.empty(n_copy, dtype=torch.float32, device="cuda") for _ in range(nrot)]
+            st = {"i": 0}
+
+            def copy_launch():
+                i = st["i"] = (st["i"] + 1) % nrot
+                B.sys_copy_f32(srcs[i], dsts[i])
+            _, c_mean, _ = time_launches(copy_launch, steps, 3)
+            copy_gbs = 8 * n_copy / c_mean / 1e9
+            del srcs, dsts
+            for proj in ("FBS", "SBM", "BFS"):
+                has = B.sys_conv1d_has(proj, w2.k_shape[0]) if w2.ndim == 1 else B.sys_conv2d_has(proj, *w2.k_shape)
+                if not has:
+                    continue
+                ln, kp = make_launcher(w2, proj, xh, tp)
+                _, k_mean, k_med = time_launches(ln, steps, 3)
+                gbs = w2.algorithmic_bytes / k_mean / 1e9
+                gtap = w2.n_taps / k_mean / 1e9
+                also.append({"workload": name, "projection": proj, "kernel_us_mean": round(k_mean * 1e6, 2),
+                             "kernel_us_median": round(k_med * 1e6, 2), "GB/s": round(gbs, 1),
+                             "Gtap/s": round(gtap, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                             "frac_fma_peak": round(gtap / FMA_PEAK_G, 4),
+                             "copy_GB/s_same_footprint": round(copy_gbs, 1),
+                             "frac_of_copy": round(gbs / copy_gbs, 3)})
+                del ln, kp
+                torch.cuda.empty_cache()
+        result["also"] = also
+
+    # ---------------------------------------------------------- CPU baseline
+    if not args.no_cpu:
+        import oracle
+        threads = oracle.threads_used(min(16, os.cpu_count() or 1))
+        t0 = time.perf_counter()
+        oracle.conv1d(x_host, taps, threads)
+        cpu_s = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        n1 = 1 << 24
+        oracle.conv1d(x_host[:n1], taps, 1)
+        cpu1_s = time.perf_counter() - t0
+        result["cpu_baseline"] = {
+            "value": round(wl.algorithmic_bytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": threads,
+            "kind": "oracle",
+            "sample": f"the whole {HEADLINE} workload once ({wl.n_taps / 1e9:.2f} G fp64 multiply-adds), "
+                      f"oracle/conv_oracle.c with {threads} OpenMP threads",
+            "seconds": round(cpu_s, 3),
+            "single_thread": {"value": round(4 * (2 * n1 - 15 + 16) / cpu1_s / 1e9, 3), "unit": "GB/s", "cores": 1,
+                              "sample": "first 2^24 inputs of the same workload", "seconds": round(cpu1_s, 3)},
+        }
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
