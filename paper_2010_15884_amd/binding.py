@@ -42,6 +42,11 @@ def lib() -> ctypes.CDLL:
             raise FileNotFoundError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2010_15884_amd.build` "
                 "(there is no fallback path)")
+        # The tensors and streams handed to the library come from torch, so both must
+        # talk to ONE HIP runtime.  torch ships its own libamdhip64 under the same soname
+        # as the system's; whichever is loaded first serves the whole process, so torch
+        # has to come first.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, fp, sz, ci = ctypes.c_void_p, ctypes.POINTER(ctypes.c_float), ctypes.c_size_t, ctypes.c_int
         L.sys_conv1d.argtypes = [vp, sz, fp, ci, vp, ci, vp]

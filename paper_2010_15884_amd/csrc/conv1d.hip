@@ -9,10 +9,15 @@
 #include "launch.h"
 #include "systolic.h"
 
+#include <cstdlib>
+
 namespace sysconv {
 namespace {
 
-constexpr int kGroups = 4;     // register groups per wavefront (R)
+#ifndef SYSCONV_1D_GROUPS
+#define SYSCONV_1D_GROUPS 4
+#endif
+constexpr int kGroups = SYSCONV_1D_GROUPS;     // register groups per wavefront (R)
 
 // ---------------------------------------------------------------- FBS ------
 // Table 2, row 3 left: PE = c, time = q.  Partial sums and weights never move;
@@ -40,11 +45,11 @@ __device__ __forceinline__ void fbs_groups_last(int nt, float (&e)[kGroups][4], 
 
 template <int KT>
 __global__ __launch_bounds__(kBlock) void conv1d_fbs_kernel(const float* __restrict__ x, float* __restrict__ y,
-                                                            long long n, long long m, int k_rt, Taps1D taps)
+                                                            long long n, long long m, int k_rt, int valid_lanes,
+                                                            Taps1D taps)
 {
     const int k = KT ? KT : k_rt;
     const int lane = threadIdx.x & (kWave - 1);
-    const int valid_lanes = kWave - halo_lanes(k);
     const long long per_group = (long long)kTile * valid_lanes;            // outputs a group yields
     const long long wave = (long long)blockIdx.x * (kBlock / kWave) + wave_in_block();
     const long long base = wave * kGroups * per_group;
@@ -127,11 +132,12 @@ __device__ __forceinline__ void sbm_groups_n(int nt, const float (&x)[kGroups][4
 
 template <int KT>
 __global__ __launch_bounds__(kBlock) void conv1d_sbm_kernel(const float* __restrict__ x, float* __restrict__ y,
-                                                            long long n, long long m, int k_rt, Taps1D taps)
+                                                            long long n, long long m, int k_rt, int valid_lanes,
+                                                            Taps1D taps)
 {
     const int k = KT ? KT : k_rt;
     const int lane = threadIdx.x & (kWave - 1);
-    const long long per_group = (long long)kTile * (kWave - halo_lanes(k));   // <= 257 - k
+    const long long per_group = (long long)kTile * valid_lanes;            // <= 257 - k
     const long long wave = (long long)blockIdx.x * (kBlock / kWave) + wave_in_block();
     const long long base = wave * kGroups * per_group;
     if (base >= m) return;
@@ -185,22 +191,38 @@ __global__ __launch_bounds__(kBlock) void conv1d_sbm_kernel(const float* __restr
     }
 }
 
+// Lanes of a group that keep their results.  At most 64 - halo_lanes(k) can; the
+// count is rounded down to a multiple of kLaneAlign so that consecutive groups
+// start on a 16*kLaneAlign-byte boundary (measured: groups that straddle 64-byte
+// lines cost ~6 % of the streaming rate).
+#ifndef SYSCONV_1D_LANE_ALIGN
+#define SYSCONV_1D_LANE_ALIGN 4
+#endif
+int group_valid_lanes(int k)
+{
+    int v = kWave - halo_lanes(k);
+    static const int forced = [] { const char* e = std::getenv("SYSCONV_1D_VALID"); return e ? std::atoi(e) : 0; }();
+    if (forced > 0 && forced <= v) return forced;
+    return v - v % SYSCONV_1D_LANE_ALIGN;
+}
+
 template <int KT, bool SBM>
 hipError_t launch_1d(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s)
 {
     Taps1D taps;
     for (int q = 0; q < kMaxK1D + 4; ++q) taps.w[q] = q < k ? w[q] : 0.0f;
     const long long m = (long long)n - k + 1;
-    const long long per_wave = (long long)kGroups * kTile * (kWave - halo_lanes(k));
+    const int valid_lanes = group_valid_lanes(k);
+    const long long per_wave = (long long)kGroups * kTile * valid_lanes;
     const long long waves = (m + per_wave - 1) / per_wave;
     const long long blocks = (waves + (kBlock / kWave) - 1) / (kBlock / kWave);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     if (SBM)
         hipLaunchKernelGGL((conv1d_sbm_kernel<KT>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
-                           x, y, (long long)n, m, k, taps);
+                           x, y, (long long)n, m, k, valid_lanes, taps);
     else
         hipLaunchKernelGGL((conv1d_fbs_kernel<KT>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
-                           x, y, (long long)n, m, k, taps);
+                           x, y, (long long)n, m, k, valid_lanes, taps);
     return hipGetLastError();
 }
 

@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kBlock) void conv2d_fbs_kernel(const float* __restr
     const int in_rows = min(kFbsTileRows + kh - 1, h - row0);
     for (int rr = wave; rr < in_rows; rr += kBlock / kWave) {
         float v[4];
-        load4_guarded(x + (long long)(row0 + rr) * xp, col0 + kTile * lane, w_img, v);
+        load4_guarded<false>(x + (long long)(row0 + rr) * xp, col0 + kTile * lane, w_img, v);
         f4 t4;
         t4.x = v[0]; t4.y = v[1]; t4.z = v[2]; t4.w = v[3];
         *reinterpret_cast<f4*>(tile + rr * kStrip + kTile * lane) = t4;
@@ -109,6 +109,10 @@ __global__ __launch_bounds__(kBlock) void conv2d_fbs_kernel(const float* __restr
     }
 }
 
+// Pointer into the kernel-argument segment (constant address space: uniform
+// reads become scalar loads).
+typedef const float __attribute__((address_space(4)))* kernarg_floats;
+
 // A zero the optimiser cannot see through (one SALU move).
 __device__ __forceinline__ int opaque_zero()
 {
@@ -129,51 +133,61 @@ __device__ __forceinline__ int opaque_zero()
 // streams from global memory through registers: no LDS.
 //
 // A wavefront walks `rows` output rows of one strip; PD input rows are in
-// flight ahead of the one being consumed.
-template <int KH, int KW, int PD>
-__global__ __launch_bounds__(kBlock) void conv2d_bfs_kernel(const float* __restrict__ x, float* __restrict__ y,
-                                                            int w_img, long long xp, int oh, int ow,
-                                                            long long yp, int rows, int row_blocks, int n_items,
-                                                            int per_xcd, Taps2D taps)
-{
-    constexpr bool kReloadTaps = KH * KW > 25;
-    const int item = xcd_contiguous(blockIdx.x, per_xcd) * (kBlock / kWave) + wave_in_block();
-    if (item >= n_items) return;                                           // uniform per wavefront
-    const int rb = item % row_blocks, strip = item / row_blocks;           // consecutive items go down a strip
-    const int lane = threadIdx.x & (kWave - 1);
-    constexpr int valid_lanes = kWave - halo_lanes(KW);
-    const int col = strip * kTile * valid_lanes + kTile * lane;
-    const int r0 = rb * rows;
-    const int rows_out = min(rows, oh - r0);
-    const int rows_in = rows_out + KH - 1;
-    const float* xrow = x + (long long)r0 * xp;
+// flight ahead of the one being consumed (PD divides KH so that the slot of a
+// row in the prefetch ring is a compile-time constant of the unrolled loop).
+// EDGE = the strip reaches past the right edge of the image: only then are
+// loads and stores bounds-checked per lane.
+enum BfsMode { kBfsFirst, kBfsMiddle, kBfsLast, kBfsChecked };
 
+template <int KH, int KW, int PD, bool EDGE>
+struct BfsStrip {
+    static_assert(KH % PD == 0, "prefetch depth must divide the filter height");
+    static constexpr bool kReloadTaps = KH * KW > 25;
+
+    const float* __restrict__ xrow;
+    float* __restrict__ yrow;
+    int col, w_img, ow, rows_out, rows_in;
+    long long xp, yp;
+    bool lane_valid;
     float ring[PD][4];
-#pragma unroll
-    for (int d = 0; d < PD; ++d) {
-        if (d < rows_in) load4_guarded(xrow + (long long)d * xp, col, w_img, ring[d]);
-        else ring[d][0] = ring[d][1] = ring[d][2] = ring[d][3] = 0.0f;
+    float acc[KH][4];
+
+    __device__ __forceinline__ void load_row(int row, float (&v)[4]) const
+    {
+        // past the end of the strip the last row is read again: an unconditional load
+        // keeps the control flow straight and the wait counts exact
+        const float* p = xrow + (long long)min(row, rows_in - 1) * xp;
+        if (EDGE) {
+            load4_guarded<false>(p, col, w_img, v);
+        } else {
+            // plain (cacheable) loads: the KH-1 halo rows are read again by the wavefront
+            // working on the next row block and should then come from L2 / the memory-side
+            // cache, not from HBM (measured on 4096^2, 5x5: 33 us against 43 us with the
+            // non-temporal hint)
+            const f4u t = *reinterpret_cast<const f4u*>(p + col);
+            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+        }
     }
 
-    float acc[KH][4];
-#pragma unroll
-    for (int s = 0; s < KH; ++s) acc[s][0] = acc[s][1] = acc[s][2] = acc[s][3] = 0.0f;
-
-    for (int rho0 = 0; rho0 < rows_in; rho0 += KH) {
+    // KH consecutive input rows rho0 .. rho0+KH-1 (rho0 a multiple of KH, so every slot
+    // index below is a compile-time constant).
+    //   kBfsFirst    rho0 == 0: output rows r = rho - p < 0 do not exist (decided statically)
+    //   kBfsMiddle   every (rho, p) pair is valid, no checks
+    //   kBfsLast     the block that holds the last input row: run-time checks
+    //   kBfsChecked  all checks at run time (one loop body for filters whose code is large)
+    template <BfsMode MODE>
+    __device__ __forceinline__ void block(int rho0, kernarg_floats taps_f)
+    {
 #pragma unroll
         for (int ph = 0; ph < KH; ++ph) {
             const int rho = rho0 + ph;
-            if (rho >= rows_in) break;
+            if ((MODE == kBfsLast || MODE == kBfsChecked) && rho >= rows_in) break;
 
             // window of input row rho: win[m] = x[rho][col + m], m < KW + 3
             float win[KW + 3];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) win[i] = ring[0][i];
-#pragma unroll
-            for (int d = 0; d + 1 < PD; ++d)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) ring[d][i] = ring[d + 1][i];
-            if (rho + PD < rows_in) load4_guarded(xrow + (long long)(rho + PD) * xp, col, w_img, ring[PD - 1]);
+            for (int i = 0; i < 4; ++i) win[i] = ring[ph % PD][i];
+            load_row(rho + PD, ring[ph % PD]);
 #pragma unroll
             for (int m = 4; m < KW + 3; ++m) win[m] = from_lane_above(win[m - 4]);
 
@@ -182,27 +196,97 @@ __global__ __launch_bounds__(kBlock) void conv2d_bfs_kernel(const float* __restr
             for (int p = 0; p < KH; ++p) {
                 const int slot = (ph - p + KH) % KH;                       // compile-time after unrolling
                 const int r = rho - p;
-                if (r >= 0 && r < rows_out) {
-                    // Small filters keep all taps in SGPRs for the whole kernel.  Larger
-                    // ones would spill them, so each filter row is re-fetched here with
-                    // scalar loads; the offset is made opaque to keep the loads in the loop.
-                    const float* fp = taps.f + p * KW + (kReloadTaps ? opaque_zero() : 0);
+                if (MODE == kBfsFirst && p > ph) continue;
+                if (MODE == kBfsChecked && r < 0) continue;
+                if ((MODE == kBfsLast || MODE == kBfsChecked) && r >= rows_out) continue;
+                // Small filters keep all taps in SGPRs for the whole kernel.  Larger ones
+                // would spill them, so each filter row is re-fetched here with scalar
+                // loads; the offset is made opaque to keep the loads in the loop.
+                kernarg_floats fp = taps_f + p * KW + (kReloadTaps ? opaque_zero() : 0);
 #pragma unroll
-                    for (int q = 0; q < KW; ++q) {
-                        const float wv = fp[q];
+                for (int q = 0; q < KW; ++q) {
+                    const float wv = fp[q];
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) acc[slot][i] = __builtin_fmaf(wv, win[q + i], acc[slot][i]);
+                    for (int i = 0; i < 4; ++i) {
+                        // the first tap of the first filter row opens a fresh partial sum
+                        if (p == 0 && q == 0) acc[slot][i] = wv * win[i];
+                        else acc[slot][i] = __builtin_fmaf(wv, win[q + i], acc[slot][i]);
                     }
                 }
             }
 
             // output row rho-(KH-1) has now seen all its filter rows
             const int done = rho - (KH - 1);
-            const int dslot = (ph + 1) % KH;
-            if (done >= 0 && lane < valid_lanes)
-                store4_guarded(y + (long long)(r0 + done) * yp, col, ow, acc[dslot]);
-            acc[dslot][0] = acc[dslot][1] = acc[dslot][2] = acc[dslot][3] = 0.0f;
+            constexpr int kh1 = KH - 1;
+            const int dslot = (ph - kh1 + KH) % KH;
+            if (MODE == kBfsFirst && ph < KH - 1) continue;
+            if (done >= 0 && done < rows_out && lane_valid) {
+                float* yr = yrow + (long long)done * yp;
+                if (EDGE) {
+                    store4_guarded(yr, col, ow, acc[dslot]);
+                } else {
+                    f4u t;
+                    t.x = acc[dslot][0]; t.y = acc[dslot][1]; t.z = acc[dslot][2]; t.w = acc[dslot][3];
+                    if (SYSCONV_NONTEMPORAL_STORE) __builtin_nontemporal_store(t, reinterpret_cast<f4u*>(yr + col));
+                    else *reinterpret_cast<f4u*>(yr + col) = t;
+                }
+            }
         }
+    }
+
+    __device__ __forceinline__ void run(kernarg_floats taps_f)
+    {
+#pragma unroll
+        for (int d = 0; d < PD; ++d) load_row(d, ring[d]);
+#pragma unroll
+        for (int s = 0; s < KH; ++s) acc[s][0] = acc[s][1] = acc[s][2] = acc[s][3] = 0.0f;
+
+        if (kReloadTaps) {
+            for (int rho0 = 0; rho0 < rows_in; rho0 += KH) block<kBfsChecked>(rho0, taps_f);
+        } else {
+            // rows_in >= KH always; the last block is the one that contains row rows_in-1
+            const int last0 = ((rows_in - 1) / KH) * KH;
+            if (last0 == 0) {
+                block<kBfsChecked>(0, taps_f);
+            } else {
+                block<kBfsFirst>(0, taps_f);
+                for (int rho0 = KH; rho0 < last0; rho0 += KH) block<kBfsMiddle>(rho0, taps_f);
+                block<kBfsLast>(last0, taps_f);
+            }
+        }
+    }
+};
+
+// The taps are the FIRST kernel argument, i.e. they sit at offset 0 of the
+// kernel-argument segment; reading them through that segment's pointer keeps
+// run-time-indexed taps on the scalar load path (indexing the by-value struct
+// itself can make the compiler copy it to scratch).
+template <int KH, int KW, int PD>
+__global__ __launch_bounds__(kBlock) void conv2d_bfs_kernel(Taps2D taps, const float* __restrict__ x,
+                                                            float* __restrict__ y, int w_img, long long xp, int oh,
+                                                            int ow, long long yp, int rows, int row_blocks,
+                                                            int n_items, int per_xcd, int valid_lanes)
+{
+    (void)taps;
+    kernarg_floats taps_f = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
+    const int item = xcd_contiguous(blockIdx.x, per_xcd) * (kBlock / kWave) + wave_in_block();
+    if (item >= n_items) return;                                           // uniform per wavefront
+    const int rb = item % row_blocks, strip = item / row_blocks;           // consecutive items go down a strip
+    const int lane = threadIdx.x & (kWave - 1);
+    const int col0 = strip * kTile * valid_lanes;
+    const int r0 = rb * rows;
+    const int rows_out = min(rows, oh - r0);
+    const float* xrow = x + (long long)r0 * xp;
+    float* yrow = y + (long long)r0 * yp;
+    const bool lane_valid = lane < valid_lanes;
+    if (col0 + kStrip <= w_img) {
+        BfsStrip<KH, KW, PD, false> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_out + KH - 1,
+                                       xp, yp, lane_valid, {}, {}};
+        st.run(taps_f);
+    } else {
+        BfsStrip<KH, KW, PD, true> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_out + KH - 1,
+                                      xp, yp, lane_valid, {}, {}};
+        st.run(taps_f);
     }
 }
 
@@ -212,6 +296,18 @@ int env_int(const char* name, int fallback)
     if (!v || !*v) return fallback;
     const int x = std::atoi(v);
     return x > 0 ? x : fallback;
+}
+
+// Lanes of a strip that keep their results: at most 64 - halo_lanes(kw).  Filters
+// small enough to be bound by memory round the count down to a multiple of 4 so
+// that strips start on 64-byte boundaries; larger ones are bound by the VALUs and
+// keep every lane they can.
+int strip_valid_lanes(int kw, int n_taps)
+{
+    const int v = kWave - halo_lanes(kw);
+    static const int forced = env_int("SYSCONV_2D_VALID", 0);
+    if (forced > 0 && forced <= v) return forced;
+    return n_taps <= 36 ? v - v % 4 : v;
 }
 
 void fill_taps(Taps2D& taps, const float* f, int n)
@@ -225,17 +321,19 @@ hipError_t launch_bfs(const float* x, int h, int w, size_t xp, const float* f, f
     Taps2D taps;
     fill_taps(taps, f, KH * KW);
     const int oh = h - KH + 1, ow = w - KW + 1;
-    constexpr int valid_lanes = kWave - halo_lanes(KW);
+    const int valid_lanes = strip_valid_lanes(KW, KH * KW);
     const int strips = (ow + kTile * valid_lanes - 1) / (kTile * valid_lanes);
-    // rows per wavefront: enough wavefronts to fill 256 CUs several times over,
-    // but tall enough that the KH-1 halo rows stay a small part of the reads
+    // Rows per wavefront.  Measured on MI355X: filters up to 5x5 are bound by memory
+    // latency and want many short items (8 rows: 29 us on 4096^2 against 33 us with 16,
+    // the re-read halo rows come from cache); larger filters are bound by the VALUs and
+    // want items tall enough that the KH-1 halo rows stay a small part of the work.
     static const int rows_env = env_int("SYSCONV_BFS_ROWS", 0);
     int rows = rows_env;
     if (rows <= 0) {
         const int want_waves = 8192;
         const int want_blocks = (want_waves + strips - 1) / strips;
         rows = (oh + want_blocks - 1) / want_blocks;
-        const int min_rows = 4 * KH > 16 ? 4 * KH : 16;
+        const int min_rows = KH <= 5 ? 8 : 2 * KH + 2;
         if (rows < min_rows) rows = min_rows;
     }
     if (rows > oh) rows = oh;
@@ -246,8 +344,8 @@ hipError_t launch_bfs(const float* x, int h, int w, size_t xp, const float* f, f
     const long long blocks = per_xcd * kXcds;
     if (blocks > 0x7fffffffLL || n_items > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL((conv2d_bfs_kernel<KH, KW, PD>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
-                       x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, (int)n_items,
-                       (int)per_xcd, taps);
+                       taps, x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, (int)n_items,
+                       (int)per_xcd, valid_lanes);
     return hipGetLastError();
 }
 
@@ -283,12 +381,12 @@ hipError_t launch_conv2d_bfs(const float* x, int h, int w, size_t xp, const floa
 {
     if (kh != kw) return hipErrorInvalidValue;
     switch (kh) {
-    case 2: return launch_bfs<2, 2, 4>(x, h, w, xp, f, y, yp, s);
-    case 3: return launch_bfs<3, 3, 4>(x, h, w, xp, f, y, yp, s);
-    case 5: return launch_bfs<5, 5, 3>(x, h, w, xp, f, y, yp, s);
-    case 7: return launch_bfs<7, 7, 2>(x, h, w, xp, f, y, yp, s);
-    case 9: return launch_bfs<9, 9, 2>(x, h, w, xp, f, y, yp, s);
-    case 11: return launch_bfs<11, 11, 2>(x, h, w, xp, f, y, yp, s);
+    case 2: return launch_bfs<2, 2, 2>(x, h, w, xp, f, y, yp, s);
+    case 3: return launch_bfs<3, 3, 3>(x, h, w, xp, f, y, yp, s);
+    case 5: return launch_bfs<5, 5, 5>(x, h, w, xp, f, y, yp, s);
+    case 7: return launch_bfs<7, 7, 7>(x, h, w, xp, f, y, yp, s);
+    case 9: return launch_bfs<9, 9, 3>(x, h, w, xp, f, y, yp, s);
+    case 11: return launch_bfs<11, 11, 1>(x, h, w, xp, f, y, yp, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -49,13 +49,25 @@ __device__ __forceinline__ float from_lane_below(float v)
         __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kDppWaveShr1, 0xf, 0xf, true));
 }
 
+// Streamed data is touched once, so by default the 16-byte accesses carry the
+// non-temporal hint (measured on MI355X: a copy moves ~6.0 TB/s with it and
+// ~5.4-5.9 TB/s without).
+#ifndef SYSCONV_NONTEMPORAL
+#define SYSCONV_NONTEMPORAL 1
+#endif
+#ifndef SYSCONV_NONTEMPORAL_STORE
+#define SYSCONV_NONTEMPORAL_STORE SYSCONV_NONTEMPORAL
+#endif
+
 // Load elements [idx, idx+4) of a row of `len` floats; elements past the end
 // read as 0 and are never dereferenced.
+template <bool NT = (SYSCONV_NONTEMPORAL != 0)>
 __device__ __forceinline__ void load4_guarded(const float* __restrict__ row, long long idx, long long len,
                                               float (&v)[4])
 {
     if (idx + 4 <= len) {
-        const f4u t = *reinterpret_cast<const f4u*>(row + idx);
+        const f4u* p = reinterpret_cast<const f4u*>(row + idx);
+        const f4u t = NT ? __builtin_nontemporal_load(p) : *p;
         v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
     } else {
 #pragma unroll
@@ -64,13 +76,16 @@ __device__ __forceinline__ void load4_guarded(const float* __restrict__ row, lon
 }
 
 // Store elements [idx, idx+4) of a row of `len` floats, clipped at the end.
+template <bool NT = (SYSCONV_NONTEMPORAL_STORE != 0)>
 __device__ __forceinline__ void store4_guarded(float* __restrict__ row, long long idx, long long len,
                                                const float (&v)[4])
 {
     if (idx + 4 <= len) {
         f4u t;
         t.x = v[0]; t.y = v[1]; t.z = v[2]; t.w = v[3];
-        *reinterpret_cast<f4u*>(row + idx) = t;
+        f4u* p = reinterpret_cast<f4u*>(row + idx);
+        if (NT) __builtin_nontemporal_store(t, p);
+        else *p = t;
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
