@@ -191,6 +191,174 @@ __global__ __launch_bounds__(kBlock) void conv1d_sbm_kernel(const float* __restr
     }
 }
 
+// ---------------------------------------------------------------- BFS ------
+// Table 2, row 2 left: PE = c, time = c + q.  At time t the input x(t) is
+// broadcast to every PE, PE c applies the weight w(t-c) that has just been
+// forwarded to it, partial sums never move.  Across 64 lanes that array would
+// idle most PEs (k of k+63 steps), so the arrays are laid along the registers:
+// every lane is an independent 4-PE array (its four consecutive outputs), the
+// inputs x(4*lane + m), m = 0..k+2, arrive one aligned float4 at a time, and
+// each arriving input is applied to the up-to-four PEs whose weight window
+// covers it.  Idle PE-steps of the paper's model cost nothing here because the
+// PEs of a lane are time-multiplexed on one ALU.  The broadcast medium is LDS:
+// a wavefront stages its 4 register groups plus a (k-1)-element halo once and
+// every lane then reads its own overlapping window with aligned ds_read_b128.
+// No lane computes garbage, and no value moves between lanes through DPP.
+//
+// One block = the four inputs m = 4b..4b+3.  wv[i] = w(4b-3+i), i = 0..6, are
+// the weights that can meet them; pair (input u, PE j) uses wv[u-j+3].  LO/HI
+// bound the valid part of wv (head block: indices below 3 are taps < 0; tail
+// blocks: indices above k+2-4b are taps >= k).
+template <int LO, int HI>
+__device__ __forceinline__ void bfs_block(float (&acc)[4], const float (&xa)[4], const float (&wv)[7])
+{
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = u - j + 3;
+            if (i >= LO && i <= HI) acc[j] = __builtin_fmaf(wv[i], xa[u], acc[j]);
+        }
+}
+
+template <int LO>
+__device__ __forceinline__ void bfs_block_hi(int hi, float (&acc)[4], const float (&xa)[4], const float (&wv)[7])
+{
+    switch (hi) {                                                          // uniform
+    case 0: bfs_block<LO, 0>(acc, xa, wv); break;
+    case 1: bfs_block<LO, 1>(acc, xa, wv); break;
+    case 2: bfs_block<LO, 2>(acc, xa, wv); break;
+    case 3: bfs_block<LO, 3>(acc, xa, wv); break;
+    case 4: bfs_block<LO, 4>(acc, xa, wv); break;
+    case 5: bfs_block<LO, 5>(acc, xa, wv); break;
+    default: bfs_block<LO, 6>(acc, xa, wv); break;
+    }
+}
+
+constexpr int kBfsLdsFloats = (kGroups + 1) * kWave * kTile;               // per wavefront: groups + halo group
+
+template <int KT>
+__global__ __launch_bounds__(kBlock) void conv1d_bfs_kernel(Taps1D taps, const float* __restrict__ x,
+                                                            float* __restrict__ y, long long n, long long m,
+                                                            int k_rt)
+{
+    __shared__ __attribute__((aligned(16))) float stage[(kBlock / kWave) * kBfsLdsFloats];
+    // taps through the kernel-argument segment (first argument = offset 0), padded in
+    // front by 3 so that w(4b-3+i) can be fetched for b = 0
+    typedef const float __attribute__((address_space(4)))* kernarg_floats;
+    kernarg_floats tw = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
+    (void)taps;
+
+    const int k = KT ? KT : k_rt;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv_id = wave_in_block();
+    const long long wave = (long long)blockIdx.x * (kBlock / kWave) + wv_id;
+    const long long base = wave * kGroups * kWave * kTile;                 // first output (= first input) of this wavefront
+    float* lds = stage + wv_id * kBfsLdsFloats;
+
+    // stage: kGroups full groups and the first k-1 (rounded up to 4) floats of the next one
+    if (base < m) {
+#pragma unroll
+        for (int r = 0; r <= kGroups; ++r) {
+            if (r < kGroups || lane < halo_lanes(k)) {
+                float v[4];
+                load4_guarded(x, base + (long long)r * kWave * kTile + kTile * lane, n, v);
+                f4 t;
+                t.x = v[0]; t.y = v[1]; t.z = v[2]; t.w = v[3];
+                *reinterpret_cast<f4*>(lds + r * kWave * kTile + kTile * lane) = t;
+            }
+        }
+    }
+    __syncthreads();                                                       // every wavefront reaches this
+    if (base >= m) return;
+
+    float acc[kGroups][4];
+#pragma unroll
+    for (int r = 0; r < kGroups; ++r) acc[r][0] = acc[r][1] = acc[r][2] = acc[r][3] = 0.0f;
+
+    auto window = [&](int r, int b, float (&xa)[4]) {
+        const f4 t = *reinterpret_cast<const f4*>(lds + r * kWave * kTile + kTile * lane + 4 * b);
+        xa[0] = t.x; xa[1] = t.y; xa[2] = t.z; xa[3] = t.w;
+    };
+    auto weights = [&](int b, float (&wv)[7]) {
+#pragma unroll
+        for (int i = 0; i < 7; ++i) wv[i] = tw[4 * b + i];               // tw[j] = w(j-3)
+    };
+
+    // head block b = 0: taps below 0 do not exist
+    {
+        float wv[7];
+        weights(0, wv);
+        const int hi = k + 2 < 6 ? k + 2 : 6;
+#pragma unroll
+        for (int r = 0; r < kGroups; ++r) {
+            float xa[4];
+            window(r, 0, xa);
+            bfs_block_hi<3>(hi, acc[r], xa, wv);
+        }
+    }
+    int b = 1;
+    // interior blocks: all sixteen (input, PE) pairs are valid
+    if (KT) {
+#pragma unroll
+        for (; 4 * b + 3 <= k - 1; ++b) {
+            float wv[7];
+            weights(b, wv);
+#pragma unroll
+            for (int r = 0; r < kGroups; ++r) {
+                float xa[4];
+                window(r, b, xa);
+                bfs_block<0, 6>(acc[r], xa, wv);
+            }
+        }
+    } else {
+#pragma nounroll
+        for (; 4 * b + 3 <= k - 1; ++b) {
+            float wv[7];
+            weights(b, wv);
+#pragma unroll
+            for (int r = 0; r < kGroups; ++r) {
+                float xa[4];
+                window(r, b, xa);
+                bfs_block<0, 6>(acc[r], xa, wv);
+            }
+        }
+    }
+    // tail blocks (at most two): taps >= k do not exist
+#pragma unroll 2
+    for (; 4 * b <= k + 2; ++b) {
+        float wv[7];
+        weights(b, wv);
+        const int hi = k + 2 - 4 * b;                                      // 0..5
+#pragma unroll
+        for (int r = 0; r < kGroups; ++r) {
+            float xa[4];
+            window(r, b, xa);
+            bfs_block_hi<0>(hi, acc[r], xa, wv);
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < kGroups; ++r)
+        store4_guarded(y, base + (long long)r * kWave * kTile + kTile * lane, m, acc[r]);
+}
+
+template <int KT>
+hipError_t launch_1d_bfs(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s)
+{
+    Taps1D taps;
+    for (int q = 0; q < kTaps1DLen; ++q) taps.w[q] = 0.0f;
+    for (int q = 0; q < k; ++q) taps.w[q + 3] = w[q];                      // three leading zeros: w(-3..-1), never multiplied
+    const long long m = (long long)n - k + 1;
+    const long long per_wave = (long long)kGroups * kWave * kTile;
+    const long long waves = (m + per_wave - 1) / per_wave;
+    const long long blocks = (waves + (kBlock / kWave) - 1) / (kBlock / kWave);
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((conv1d_bfs_kernel<KT>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
+                       taps, x, y, (long long)n, m, k);
+    return hipGetLastError();
+}
+
 // Lanes of a group that keep their results.  At most 64 - halo_lanes(k) can; the
 // count is rounded down to a multiple of kLaneAlign so that consecutive groups
 // start on a 16*kLaneAlign-byte boundary (measured: groups that straddle 64-byte
@@ -210,7 +378,7 @@ template <int KT, bool SBM>
 hipError_t launch_1d(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s)
 {
     Taps1D taps;
-    for (int q = 0; q < kMaxK1D + 4; ++q) taps.w[q] = q < k ? w[q] : 0.0f;
+    for (int q = 0; q < kTaps1DLen; ++q) taps.w[q] = q < k ? w[q] : 0.0f;
     const long long m = (long long)n - k + 1;
     const int valid_lanes = group_valid_lanes(k);
     const long long per_wave = (long long)kGroups * kTile * valid_lanes;
@@ -252,11 +420,15 @@ hipError_t launch_conv1d_sbm(const float* x, size_t n, const float* w, int k, fl
     return launch_by_k<true>(x, n, w, k, y, s);
 }
 
-bool has_conv1d_bfs(int) { return false; }
+bool has_conv1d_bfs(int k) { return k >= 1 && k <= kMaxK1D; }
 
-hipError_t launch_conv1d_bfs(const float*, size_t, const float*, int, float*, hipStream_t)
+hipError_t launch_conv1d_bfs(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s)
 {
-    return hipErrorNotSupported;
+    switch (k) {
+    case 5: return launch_1d_bfs<5>(x, n, w, k, y, s);
+    case 16: return launch_1d_bfs<16>(x, n, w, k, y, s);
+    default: return launch_1d_bfs<0>(x, n, w, k, y, s);
+    }
 }
 
 }  // namespace sysconv

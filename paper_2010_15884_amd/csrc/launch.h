@@ -14,7 +14,8 @@ constexpr int kMaxK2D = 15;
 // Tap blocks travel by value in the kernel-argument segment (uniform scalar
 // loads, no device allocation).  Padded so that a block of four taps can
 // always be fetched.
-struct Taps1D { float w[kMaxK1D + 4]; };
+constexpr int kTaps1DLen = kMaxK1D + 12;      // room for a 3-tap lead-in and a 7-wide fetch at the end
+struct Taps1D { float w[kTaps1DLen]; };
 struct Taps2D { float f[kMaxK2D * kMaxK2D + 7]; };
 
 hipError_t launch_conv1d_fbs(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s);
