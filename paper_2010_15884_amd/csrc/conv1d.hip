@@ -130,6 +130,26 @@ __device__ __forceinline__ void sbm_groups_n(int nt, const float (&x)[kGroups][4
     }
 }
 
+__device__ __forceinline__ void sbm_readout_lane(float (&z)[kGroups][4])
+{
+#pragma unroll
+    for (int r = 0; r < kGroups; ++r)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) z[r][i] = from_lane_above(z[r][i]);
+}
+
+template <int N>
+__device__ __forceinline__ void sbm_readout_pe(float (&z)[kGroups][4])
+{
+#pragma unroll
+    for (int r = 0; r < kGroups; ++r)
+#pragma unroll
+        for (int t = 0; t < N; ++t) {
+            const float above = from_lane_above(z[r][0]);
+            z[r][0] = z[r][1]; z[r][1] = z[r][2]; z[r][2] = z[r][3]; z[r][3] = above;
+        }
+}
+
 template <int KT>
 __global__ __launch_bounds__(kBlock) void conv1d_sbm_kernel(const float* __restrict__ x, float* __restrict__ y,
                                                             long long n, long long m, int k_rt, int valid_lanes,
@@ -173,21 +193,29 @@ __global__ __launch_bounds__(kBlock) void conv1d_sbm_kernel(const float* __restr
         sbm_groups_n<false>(k - q, xs, z, w);                              // 1..3 taps left
     }
 
-    // PE s = 4*lane + i of group r holds output  base + r*per_group + s - (k-1)
-    // provided 0 <= s - (k-1) < per_group.
-    const long long o0 = (long long)kTile * lane - (k - 1);
+    // PE s = 4*lane + i of group r now holds output  base + r*per_group + s - (k-1).
+    // Read the result vector out k-1 PEs further down (the `Z.select<CCC>(Q-1)` region
+    // read of the paper's SBM listing): a whole lane at a time while four or more PEs
+    // remain, then PE by PE.  After that PE s holds output s and the stores line up
+    // with the loads.
+    int left = k - 1;
+    if (KT) {
 #pragma unroll
-    for (int r = 0; r < kGroups; ++r) {
-        const long long gbase = base + r * per_group;
-        if (o0 >= 0 && o0 + 4 <= per_group) {
-            store4_guarded(y, gbase + o0, m, z[r]);
-        } else {
+        for (; left >= 4; left -= 4) sbm_readout_lane(z);
+    } else {
+#pragma nounroll
+        for (; left >= 4; left -= 4) sbm_readout_lane(z);
+    }
+    switch (left) {                                                        // uniform
+    case 3: sbm_readout_pe<3>(z); break;
+    case 2: sbm_readout_pe<2>(z); break;
+    case 1: sbm_readout_pe<1>(z); break;
+    default: break;
+    }
+    if (lane < valid_lanes) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const long long o = o0 + i;
-                if (o >= 0 && o < per_group && gbase + o < m) y[gbase + o] = z[r][i];
-            }
-        }
+        for (int r = 0; r < kGroups; ++r)
+            store4_guarded(y, base + r * per_group + kTile * lane, m, z[r]);
     }
 }
 

@@ -290,6 +290,120 @@ __global__ __launch_bounds__(kBlock) void conv2d_bfs_kernel(Taps2D taps, const f
     }
 }
 
+// ------------------------------------------------------------- SBM 2-D -----
+// Section 5 (two projections): PE = c + q, time = p + P*q, the row loop r stays
+// outside.  Every PE keeps a KH-tall column of inputs x(r..r+KH-1, s); the
+// partial sum of output (r, c) starts at PE c, takes the KH products of filter
+// column q there, and moves one PE up each time q advances, so after KH*KW steps
+// PE c + KW - 1 holds it.  A wavefront owns a strip of 256 PEs (image columns)
+// and walks down the rows with a ring of KH + PD input rows in registers (KH in
+// use, PD in flight); the ring is indexed by row mod (KH+PD) and the row loop is
+// unrolled that many times so that all indices are compile-time constants.
+// Before storing, the result vector is read out KW-1 PEs further down (the
+// paper's `Z.select<CCC>(Q-1)` region read), which lines the stores up with the
+// loads.  Taps arrive transposed (filter column q contiguous).
+template <int KH, int KW, int PD, bool EDGE>
+struct SbmStrip {
+    static constexpr int RS = KH + PD;                                     // ring size
+    static constexpr bool kReloadTaps = KH * KW > 25;
+
+    const float* __restrict__ xrow;
+    float* __restrict__ yrow;
+    int col, w_img, ow, rows_out, rows_in;
+    long long xp, yp;
+    bool lane_valid;
+    float ring[RS][4];
+
+    __device__ __forceinline__ void load_row(int row, float (&v)[4]) const
+    {
+        const float* p = xrow + (long long)min(row, rows_in - 1) * xp;
+        if (EDGE) {
+            load4_guarded<false>(p, col, w_img, v);
+        } else {
+            const f4u t = *reinterpret_cast<const f4u*>(p + col);
+            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+        }
+    }
+
+    __device__ __forceinline__ void run(kernarg_floats taps_t)
+    {
+#pragma unroll
+        for (int d = 0; d < RS - 1; ++d) load_row(d, ring[d]);
+
+        for (int r0 = 0; r0 < rows_out; r0 += RS) {
+#pragma unroll
+            for (int ph = 0; ph < RS; ++ph) {
+                const int r = r0 + ph;
+                if (r >= rows_out) break;
+                // the slot of row r-1 is free now: fetch row r+KH+PD-1 into it
+                load_row(r + RS - 1, ring[(ph + RS - 1) % RS]);
+
+                float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int q = 0; q < KW; ++q) {
+                    if (q > 0) {                                           // Z(s) <- Z(s-1)
+                        const float below = from_lane_below(z[3]);
+                        z[3] = z[2]; z[2] = z[1]; z[1] = z[0]; z[0] = below;
+                    }
+                    kernarg_floats ft = taps_t + q * KH + (kReloadTaps ? opaque_zero() : 0);
+#pragma unroll
+                    for (int p = 0; p < KH; ++p) {
+                        const float wv = ft[p];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) z[i] = __builtin_fmaf(wv, ring[(ph + p) % RS][i], z[i]);
+                    }
+                }
+                // read the results out KW-1 PEs further down: PE s gets output column s
+#pragma unroll
+                for (int t = 0; t < KW - 1; ++t) {
+                    const float above = from_lane_above(z[0]);
+                    z[0] = z[1]; z[1] = z[2]; z[2] = z[3]; z[3] = above;
+                }
+                if (lane_valid) {
+                    float* yr = yrow + (long long)r * yp;
+                    if (EDGE) {
+                        store4_guarded(yr, col, ow, z);
+                    } else {
+                        f4u t;
+                        t.x = z[0]; t.y = z[1]; t.z = z[2]; t.w = z[3];
+                        if (SYSCONV_NONTEMPORAL_STORE) __builtin_nontemporal_store(t, reinterpret_cast<f4u*>(yr + col));
+                        else *reinterpret_cast<f4u*>(yr + col) = t;
+                    }
+                }
+            }
+        }
+    }
+};
+
+template <int KH, int KW, int PD>
+__global__ __launch_bounds__(kBlock) void conv2d_sbm_kernel(Taps2D taps_t, const float* __restrict__ x,
+                                                            float* __restrict__ y, int w_img, long long xp, int oh,
+                                                            int ow, long long yp, int rows, int row_blocks,
+                                                            int n_items, int per_xcd, int valid_lanes)
+{
+    (void)taps_t;
+    kernarg_floats tf = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
+    const int item = xcd_contiguous(blockIdx.x, per_xcd) * (kBlock / kWave) + wave_in_block();
+    if (item >= n_items) return;
+    const int rb = item % row_blocks, strip = item / row_blocks;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int col0 = strip * kTile * valid_lanes;
+    const int r0 = rb * rows;
+    const int rows_out = min(rows, oh - r0);
+    const float* xrow = x + (long long)r0 * xp;
+    float* yrow = y + (long long)r0 * yp;
+    const bool lane_valid = lane < valid_lanes;
+    if (col0 + kStrip <= w_img) {
+        SbmStrip<KH, KW, PD, false> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_out + KH - 1,
+                                       xp, yp, lane_valid, {}};
+        st.run(tf);
+    } else {
+        SbmStrip<KH, KW, PD, true> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_out + KH - 1,
+                                      xp, yp, lane_valid, {}};
+        st.run(tf);
+    }
+}
+
 int env_int(const char* name, int fallback)
 {
     const char* v = std::getenv(name);
@@ -315,11 +429,19 @@ void fill_taps(Taps2D& taps, const float* f, int n)
     for (int i = 0; i < kMaxK2D * kMaxK2D + 7; ++i) taps.f[i] = i < n ? f[i] : 0.0f;
 }
 
-template <int KH, int KW, int PD>
-hipError_t launch_bfs(const float* x, int h, int w, size_t xp, const float* f, float* y, size_t yp, hipStream_t s)
+// Shared launcher of the two strip-walking kernels (BFS and SBM).
+template <int KH, int KW, int PD, bool SBM>
+hipError_t launch_strip(const float* x, int h, int w, size_t xp, const float* f, float* y, size_t yp, hipStream_t s)
 {
     Taps2D taps;
-    fill_taps(taps, f, KH * KW);
+    if (SBM) {                                                             // filter column q contiguous
+        float ft[KH * KW];
+        for (int p = 0; p < KH; ++p)
+            for (int q = 0; q < KW; ++q) ft[q * KH + p] = f[p * KW + q];
+        fill_taps(taps, ft, KH * KW);
+    } else {
+        fill_taps(taps, f, KH * KW);
+    }
     const int oh = h - KH + 1, ow = w - KW + 1;
     const int valid_lanes = strip_valid_lanes(KW, KH * KW);
     const int strips = (ow + kTile * valid_lanes - 1) / (kTile * valid_lanes);
@@ -343,9 +465,14 @@ hipError_t launch_bfs(const float* x, int h, int w, size_t xp, const float* f, f
     const long long per_xcd = (groups + kXcds - 1) / kXcds;
     const long long blocks = per_xcd * kXcds;
     if (blocks > 0x7fffffffLL || n_items > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((conv2d_bfs_kernel<KH, KW, PD>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
-                       taps, x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, (int)n_items,
-                       (int)per_xcd, valid_lanes);
+    if constexpr (SBM)
+        hipLaunchKernelGGL((conv2d_sbm_kernel<KH, KW, PD>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
+                           taps, x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, (int)n_items,
+                           (int)per_xcd, valid_lanes);
+    else
+        hipLaunchKernelGGL((conv2d_bfs_kernel<KH, KW, PD>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
+                           taps, x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, (int)n_items,
+                           (int)per_xcd, valid_lanes);
     return hipGetLastError();
 }
 
@@ -381,21 +508,31 @@ hipError_t launch_conv2d_bfs(const float* x, int h, int w, size_t xp, const floa
 {
     if (kh != kw) return hipErrorInvalidValue;
     switch (kh) {
-    case 2: return launch_bfs<2, 2, 2>(x, h, w, xp, f, y, yp, s);
-    case 3: return launch_bfs<3, 3, 3>(x, h, w, xp, f, y, yp, s);
-    case 5: return launch_bfs<5, 5, 5>(x, h, w, xp, f, y, yp, s);
-    case 7: return launch_bfs<7, 7, 7>(x, h, w, xp, f, y, yp, s);
-    case 9: return launch_bfs<9, 9, 3>(x, h, w, xp, f, y, yp, s);
-    case 11: return launch_bfs<11, 11, 1>(x, h, w, xp, f, y, yp, s);
+    case 2: return launch_strip<2, 2, 2, false>(x, h, w, xp, f, y, yp, s);
+    case 3: return launch_strip<3, 3, 3, false>(x, h, w, xp, f, y, yp, s);
+    case 5: return launch_strip<5, 5, 5, false>(x, h, w, xp, f, y, yp, s);
+    case 7: return launch_strip<7, 7, 7, false>(x, h, w, xp, f, y, yp, s);
+    case 9: return launch_strip<9, 9, 3, false>(x, h, w, xp, f, y, yp, s);
+    case 11: return launch_strip<11, 11, 1, false>(x, h, w, xp, f, y, yp, s);
     default: return hipErrorInvalidValue;
     }
 }
 
-bool has_conv2d_sbm(int, int) { return false; }
+bool has_conv2d_sbm(int kh, int kw) { return has_conv2d_bfs(kh, kw); }
 
-hipError_t launch_conv2d_sbm(const float*, int, int, size_t, const float*, int, int, float*, size_t, hipStream_t)
+hipError_t launch_conv2d_sbm(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
+                             float* y, size_t yp, hipStream_t s)
 {
-    return hipErrorNotSupported;
+    if (kh != kw) return hipErrorInvalidValue;
+    switch (kh) {
+    case 2: return launch_strip<2, 2, 2, true>(x, h, w, xp, f, y, yp, s);
+    case 3: return launch_strip<3, 3, 3, true>(x, h, w, xp, f, y, yp, s);
+    case 5: return launch_strip<5, 5, 3, true>(x, h, w, xp, f, y, yp, s);
+    case 7: return launch_strip<7, 7, 2, true>(x, h, w, xp, f, y, yp, s);
+    case 9: return launch_strip<9, 9, 2, true>(x, h, w, xp, f, y, yp, s);
+    case 11: return launch_strip<11, 11, 1, true>(x, h, w, xp, f, y, yp, s);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace sysconv
