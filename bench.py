@@ -104,6 +104,13 @@ def main() -> int:
 
     def time_launches(launch, steps, warmup):
         """(wall seconds for `steps` launches, mean per-launch seconds from HIP events)."""
+        # the GPU drops its clocks while the host prepares inputs: keep it busy for ~50 ms
+        # first so that the timed launches see steady-state clocks, then the W warm-up steps
+        t_spin = time.perf_counter()
+        while time.perf_counter() - t_spin < 0.05:
+            for _ in range(8):
+                launch()
+            torch.cuda.synchronize()
         for _ in range(warmup):
             launch()
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
@@ -206,7 +213,7 @@ def main() -> int:
                              "copy_GB/s_same_footprint": round(copy_gbs, 1),
                              "frac_of_copy": round(gbs / copy_gbs, 3)})
                 del ln, kp
-                torch.cuda.empty_cache()
+                pass
         result["also"] = also
 
     # ---------------------------------------------------------- CPU baseline

@@ -96,7 +96,10 @@ int sys_conv2d(const float* d_x, int h, int w, size_t x_pitch, const float* h_f,
     if (ranges_overlap(d_x, x_bytes, d_y, y_bytes)) return SYS_ERR_ALIAS;
 
     int proj = projection;
-    if (proj == SYS_PROJ_AUTO) proj = sysconv::has_conv2d_bfs(kh, kw) ? SYS_PROJ_BFS : SYS_PROJ_FBS;
+    // measured order on MI355X: SBM >= BFS > FBS wherever the strip kernels are built
+    if (proj == SYS_PROJ_AUTO)
+        proj = sysconv::has_conv2d_sbm(kh, kw) ? SYS_PROJ_SBM
+             : sysconv::has_conv2d_bfs(kh, kw) ? SYS_PROJ_BFS : SYS_PROJ_FBS;
     switch (proj) {
     case SYS_PROJ_FBS:
         return hip_status(sysconv::launch_conv2d_fbs(d_x, h, w, x_pitch, h_f, kh, kw, d_y, y_pitch, stream));

@@ -113,6 +113,21 @@ __global__ __launch_bounds__(kBlock) void conv2d_fbs_kernel(const float* __restr
 // reads become scalar loads).
 typedef const float __attribute__((address_space(4)))* kernarg_floats;
 
+// Work item -> (row block, strip).  order 0: consecutive items go down a strip and
+// every XCD owns whole strips; order 1: consecutive items go along a band of rows
+// and every XCD owns whole bands.
+__device__ __forceinline__ void decode_item(int item, int row_blocks, int n_items, int order, int& rb, int& strip)
+{
+    if (order == 0 || order == 4) {
+        rb = item % row_blocks;
+        strip = item / row_blocks;
+    } else {
+        const int strips = n_items / row_blocks;
+        rb = item / strips;
+        strip = item % strips;
+    }
+}
+
 // A zero the optimiser cannot see through (one SALU move).
 __device__ __forceinline__ int opaque_zero()
 {
@@ -265,26 +280,28 @@ template <int KH, int KW, int PD>
 __global__ __launch_bounds__(kBlock) void conv2d_bfs_kernel(Taps2D taps, const float* __restrict__ x,
                                                             float* __restrict__ y, int w_img, long long xp, int oh,
                                                             int ow, long long yp, int rows, int row_blocks,
-                                                            int n_items, int per_xcd, int valid_lanes)
+                                                            int n_items, int per_xcd, int valid_lanes, int order)
 {
     (void)taps;
     kernarg_floats taps_f = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
-    const int item = xcd_contiguous(blockIdx.x, per_xcd) * (kBlock / kWave) + wave_in_block();
+    const int item = (order == 2 || order == 4 ? (int)blockIdx.x : xcd_contiguous(blockIdx.x, per_xcd)) * (kBlock / kWave) + wave_in_block();
     if (item >= n_items) return;                                           // uniform per wavefront
-    const int rb = item % row_blocks, strip = item / row_blocks;           // consecutive items go down a strip
+    int rb, strip;
+    decode_item(item, row_blocks, n_items, order, rb, strip);
     const int lane = threadIdx.x & (kWave - 1);
     const int col0 = strip * kTile * valid_lanes;
     const int r0 = rb * rows;
     const int rows_out = min(rows, oh - r0);
+    const int rows_in = rows_out + KH - 1;
     const float* xrow = x + (long long)r0 * xp;
     float* yrow = y + (long long)r0 * yp;
     const bool lane_valid = lane < valid_lanes;
     if (col0 + kStrip <= w_img) {
-        BfsStrip<KH, KW, PD, false> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_out + KH - 1,
+        BfsStrip<KH, KW, PD, false> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_in,
                                        xp, yp, lane_valid, {}, {}};
         st.run(taps_f);
     } else {
-        BfsStrip<KH, KW, PD, true> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_out + KH - 1,
+        BfsStrip<KH, KW, PD, true> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_in,
                                       xp, yp, lane_valid, {}, {}};
         st.run(taps_f);
     }
@@ -379,26 +396,28 @@ template <int KH, int KW, int PD>
 __global__ __launch_bounds__(kBlock) void conv2d_sbm_kernel(Taps2D taps_t, const float* __restrict__ x,
                                                             float* __restrict__ y, int w_img, long long xp, int oh,
                                                             int ow, long long yp, int rows, int row_blocks,
-                                                            int n_items, int per_xcd, int valid_lanes)
+                                                            int n_items, int per_xcd, int valid_lanes, int order)
 {
     (void)taps_t;
     kernarg_floats tf = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
-    const int item = xcd_contiguous(blockIdx.x, per_xcd) * (kBlock / kWave) + wave_in_block();
+    const int item = (order == 2 || order == 4 ? (int)blockIdx.x : xcd_contiguous(blockIdx.x, per_xcd)) * (kBlock / kWave) + wave_in_block();
     if (item >= n_items) return;
-    const int rb = item % row_blocks, strip = item / row_blocks;
+    int rb, strip;
+    decode_item(item, row_blocks, n_items, order, rb, strip);
     const int lane = threadIdx.x & (kWave - 1);
     const int col0 = strip * kTile * valid_lanes;
     const int r0 = rb * rows;
     const int rows_out = min(rows, oh - r0);
+    const int rows_in = rows_out + KH - 1;
     const float* xrow = x + (long long)r0 * xp;
     float* yrow = y + (long long)r0 * yp;
     const bool lane_valid = lane < valid_lanes;
     if (col0 + kStrip <= w_img) {
-        SbmStrip<KH, KW, PD, false> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_out + KH - 1,
+        SbmStrip<KH, KW, PD, false> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_in,
                                        xp, yp, lane_valid, {}};
         st.run(tf);
     } else {
-        SbmStrip<KH, KW, PD, true> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_out + KH - 1,
+        SbmStrip<KH, KW, PD, true> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_in,
                                       xp, yp, lane_valid, {}};
         st.run(tf);
     }
@@ -412,16 +431,14 @@ int env_int(const char* name, int fallback)
     return x > 0 ? x : fallback;
 }
 
-// Lanes of a strip that keep their results: at most 64 - halo_lanes(kw).  Filters
-// small enough to be bound by memory round the count down to a multiple of 4 so
-// that strips start on 64-byte boundaries; larger ones are bound by the VALUs and
-// keep every lane they can.
-int strip_valid_lanes(int kw, int n_taps)
+// Lanes of a strip that keep their results: 64 - halo_lanes(kw).  (Rounding the
+// strip width down to whole cache lines was measured and does not pay in 2-D:
+// 4096^2, 5x5: 28.1 us with 63 lanes, 29.0 with 60, 29.3 with 56.)
+int strip_valid_lanes(int kw)
 {
     const int v = kWave - halo_lanes(kw);
-    static const int forced = env_int("SYSCONV_2D_VALID", 0);
-    if (forced > 0 && forced <= v) return forced;
-    return n_taps <= 36 ? v - v % 4 : v;
+    const int forced = env_int("SYSCONV_2D_VALID", 0);
+    return (forced > 0 && forced <= v) ? forced : v;
 }
 
 void fill_taps(Taps2D& taps, const float* f, int n)
@@ -433,31 +450,25 @@ void fill_taps(Taps2D& taps, const float* f, int n)
 template <int KH, int KW, int PD, bool SBM>
 hipError_t launch_strip(const float* x, int h, int w, size_t xp, const float* f, float* y, size_t yp, hipStream_t s)
 {
+    // BFS reads its taps row by row, SBM column by column (transposed)
     Taps2D taps;
-    if (SBM) {                                                             // filter column q contiguous
-        float ft[KH * KW];
-        for (int p = 0; p < KH; ++p)
-            for (int q = 0; q < KW; ++q) ft[q * KH + p] = f[p * KW + q];
-        fill_taps(taps, ft, KH * KW);
-    } else {
-        fill_taps(taps, f, KH * KW);
-    }
+    float ft[KH * KW];
+    for (int p = 0; p < KH; ++p)
+        for (int q = 0; q < KW; ++q) ft[SBM ? q * KH + p : p * KW + q] = f[p * KW + q];
+    fill_taps(taps, ft, KH * KW);
     const int oh = h - KH + 1, ow = w - KW + 1;
-    const int valid_lanes = strip_valid_lanes(KW, KH * KW);
+    const int valid_lanes = strip_valid_lanes(KW);
     const int strips = (ow + kTile * valid_lanes - 1) / (kTile * valid_lanes);
-    // Rows per wavefront.  Measured on MI355X: filters up to 5x5 are bound by memory
-    // latency and want many short items (8 rows: 29 us on 4096^2 against 33 us with 16,
-    // the re-read halo rows come from cache); larger filters are bound by the VALUs and
-    // want items tall enough that the KH-1 halo rows stay a small part of the work.
-    static const int rows_env = env_int("SYSCONV_BFS_ROWS", 0);
+    // Rows per wavefront.  Measured on MI355X (in-process A/B sweeps): short items win
+    // everywhere -- small filters are bound by memory latency and need > 8 K wavefronts
+    // in flight (4096^2, 5x5, SBM: 27 us with 4 rows, 30 us with 16), large ones are
+    // bound by the VALUs and lose to the tail of a coarse decomposition (8192^2, 11x11,
+    // SBM: 246 us with 8 rows, 266 us with 24, 317 us with 64).  BFS pays KH(KH-1)/2
+    // skipped filter-row blocks per item, so its items are a little taller.  The halo
+    // rows that short items re-read come mostly from cache.
+    const int rows_env = env_int("SYSCONV_BFS_ROWS", 0);
     int rows = rows_env;
-    if (rows <= 0) {
-        const int want_waves = 8192;
-        const int want_blocks = (want_waves + strips - 1) / strips;
-        rows = (oh + want_blocks - 1) / want_blocks;
-        const int min_rows = KH <= 5 ? 8 : 2 * KH + 2;
-        if (rows < min_rows) rows = min_rows;
-    }
+    if (rows <= 0) rows = SBM ? (KH <= 5 ? 4 : 8) : (KH <= 5 ? 6 : 16);
     if (rows > oh) rows = oh;
     const int row_blocks = (oh + rows - 1) / rows;
     const long long n_items = (long long)row_blocks * strips;
@@ -465,14 +476,15 @@ hipError_t launch_strip(const float* x, int h, int w, size_t xp, const float* f,
     const long long per_xcd = (groups + kXcds - 1) / kXcds;
     const long long blocks = per_xcd * kXcds;
     if (blocks > 0x7fffffffLL || n_items > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const int order = env_int("SYSCONV_2D_ORDER", 0);
     if constexpr (SBM)
         hipLaunchKernelGGL((conv2d_sbm_kernel<KH, KW, PD>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
                            taps, x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, (int)n_items,
-                           (int)per_xcd, valid_lanes);
+                           (int)per_xcd, valid_lanes, order);
     else
         hipLaunchKernelGGL((conv2d_bfs_kernel<KH, KW, PD>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
                            taps, x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, (int)n_items,
-                           (int)per_xcd, valid_lanes);
+                           (int)per_xcd, valid_lanes, order);
     return hipGetLastError();
 }
 

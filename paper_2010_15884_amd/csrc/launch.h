@@ -16,7 +16,9 @@ constexpr int kMaxK2D = 15;
 // always be fetched.
 constexpr int kTaps1DLen = kMaxK1D + 12;      // room for a 3-tap lead-in and a 7-wide fetch at the end
 struct Taps1D { float w[kTaps1DLen]; };
-struct Taps2D { float f[kMaxK2D * kMaxK2D + 7]; };
+constexpr int kTaps2DLen = kMaxK2D * kMaxK2D + 7;
+struct Taps2D { float f[kTaps2DLen]; };
+
 
 hipError_t launch_conv1d_fbs(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s);
 hipError_t launch_conv1d_sbm(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s);
