@@ -113,21 +113,6 @@ __global__ __launch_bounds__(kBlock) void conv2d_fbs_kernel(const float* __restr
 // reads become scalar loads).
 typedef const float __attribute__((address_space(4)))* kernarg_floats;
 
-// Work item -> (row block, strip).  order 0: consecutive items go down a strip and
-// every XCD owns whole strips; order 1: consecutive items go along a band of rows
-// and every XCD owns whole bands.
-__device__ __forceinline__ void decode_item(int item, int row_blocks, int n_items, int order, int& rb, int& strip)
-{
-    if (order == 0 || order == 4) {
-        rb = item % row_blocks;
-        strip = item / row_blocks;
-    } else {
-        const int strips = n_items / row_blocks;
-        rb = item / strips;
-        strip = item % strips;
-    }
-}
-
 // A zero the optimiser cannot see through (one SALU move).
 __device__ __forceinline__ int opaque_zero()
 {
@@ -158,20 +143,36 @@ template <int KH, int KW, int PD, bool EDGE>
 struct BfsStrip {
     static_assert(KH % PD == 0, "prefetch depth must divide the filter height");
     static constexpr bool kReloadTaps = KH * KW > 25;
+    static constexpr int NH = (KW + 2) / 4;                                // halo float4s: ceil((KW-1)/4)
 
     const float* __restrict__ xrow;
     float* __restrict__ yrow;
     int col, w_img, ow, rows_out, rows_in;
     long long xp, yp;
-    bool lane_valid;
+    bool last_lane;                        // lane 63: the lane the halo enters through
     float ring[PD][4];
+    float halo[PD][NH][4];                 // meaningful in lane 63 only
     float acc[KH][4];
 
-    __device__ __forceinline__ void load_row(int row, float (&v)[4]) const
+    __device__ __forceinline__ void load_row(int row, float (&v)[4], float (&h)[NH][4]) const
     {
         // past the end of the strip the last row is read again: an unconditional load
         // keeps the control flow straight and the wait counts exact
         const float* p = xrow + (long long)min(row, rows_in - 1) * xp;
+        // Halo: the KW-1 columns right of the strip, fetched by lane 63 alone (one
+        // 16-byte access per float4) into the registers that the window hand-overs
+        // leave untouched in that lane.
+        if (last_lane) {
+#pragma unroll
+            for (int j = 0; j < NH; ++j) {
+                if (EDGE) {
+                    load4_guarded<false>(p, col + 4 * (j + 1), w_img, h[j]);
+                } else {
+                    const f4u t = *reinterpret_cast<const f4u*>(p + col + 4 * (j + 1));
+                    h[j][0] = t.x; h[j][1] = t.y; h[j][2] = t.z; h[j][3] = t.w;
+                }
+            }
+        }
         if (EDGE) {
             load4_guarded<false>(p, col, w_img, v);
         } else {
@@ -200,11 +201,18 @@ struct BfsStrip {
 
             // window of input row rho: win[m] = x[rho][col + m], m < KW + 3
             float win[KW + 3];
+            float hin[NH][4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) win[i] = ring[ph % PD][i];
-            load_row(rho + PD, ring[ph % PD]);
 #pragma unroll
-            for (int m = 4; m < KW + 3; ++m) win[m] = from_lane_above(win[m - 4]);
+            for (int j = 0; j < NH; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) hin[j][i] = halo[ph % PD][j][i];
+            load_row(rho + PD, ring[ph % PD], halo[ph % PD]);
+            // X(c) <- X(c+1): lanes 0..62 take the value of the lane above, lane 63 takes
+            // the next halo element
+#pragma unroll
+            for (int m = 4; m < KW + 3; ++m) win[m] = from_lane_above_or(win[m - 4], hin[(m - 4) / 4][(m - 4) % 4]);
 
             // broadcast the row to the KH partial-sum vectors it feeds
 #pragma unroll
@@ -235,7 +243,7 @@ struct BfsStrip {
             constexpr int kh1 = KH - 1;
             const int dslot = (ph - kh1 + KH) % KH;
             if (MODE == kBfsFirst && ph < KH - 1) continue;
-            if (done >= 0 && done < rows_out && lane_valid) {
+            if (done >= 0 && done < rows_out) {
                 float* yr = yrow + (long long)done * yp;
                 if (EDGE) {
                     store4_guarded(yr, col, ow, acc[dslot]);
@@ -252,7 +260,7 @@ struct BfsStrip {
     __device__ __forceinline__ void run(kernarg_floats taps_f)
     {
 #pragma unroll
-        for (int d = 0; d < PD; ++d) load_row(d, ring[d]);
+        for (int d = 0; d < PD; ++d) load_row(d, ring[d], halo[d]);
 #pragma unroll
         for (int s = 0; s < KH; ++s) acc[s][0] = acc[s][1] = acc[s][2] = acc[s][3] = 0.0f;
 
@@ -280,29 +288,33 @@ template <int KH, int KW, int PD>
 __global__ __launch_bounds__(kBlock) void conv2d_bfs_kernel(Taps2D taps, const float* __restrict__ x,
                                                             float* __restrict__ y, int w_img, long long xp, int oh,
                                                             int ow, long long yp, int rows, int row_blocks,
-                                                            int n_items, int per_xcd, int valid_lanes, int order)
+                                                            int n_items, int per_xcd, int valid_lanes)
 {
     (void)taps;
+    (void)valid_lanes;
     kernarg_floats taps_f = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
-    const int item = (order == 2 || order == 4 ? (int)blockIdx.x : xcd_contiguous(blockIdx.x, per_xcd)) * (kBlock / kWave) + wave_in_block();
+    const int item = xcd_contiguous(blockIdx.x, per_xcd) * (kBlock / kWave) + wave_in_block();
     if (item >= n_items) return;                                           // uniform per wavefront
-    int rb, strip;
-    decode_item(item, row_blocks, n_items, order, rb, strip);
+    // consecutive items go down a strip, and every XCD owns a contiguous run of items:
+    // the row blocks that share halo rows meet in one L2 (measured against row-major
+    // and plain round-robin orders on 4096^2, 5x5: 35 us vs 37-41 us)
+    const int rb = item % row_blocks, strip = item / row_blocks;
     const int lane = threadIdx.x & (kWave - 1);
-    const int col0 = strip * kTile * valid_lanes;
+    const int col0 = strip * kStrip;                                       // strips are 256 outputs wide
     const int r0 = rb * rows;
     const int rows_out = min(rows, oh - r0);
     const int rows_in = rows_out + KH - 1;
     const float* xrow = x + (long long)r0 * xp;
     float* yrow = y + (long long)r0 * yp;
-    const bool lane_valid = lane < valid_lanes;
-    if (col0 + kStrip <= w_img) {
+    const bool last_lane = lane == kWave - 1;
+    constexpr int halo_cols = kTile * ((KW + 2) / 4);
+    if (col0 + kStrip + halo_cols <= w_img) {
         BfsStrip<KH, KW, PD, false> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_in,
-                                       xp, yp, lane_valid, {}, {}};
+                                       xp, yp, last_lane, {}, {}, {}};
         st.run(taps_f);
     } else {
         BfsStrip<KH, KW, PD, true> st{xrow, yrow, col0 + kTile * lane, w_img, ow, rows_out, rows_in,
-                                      xp, yp, lane_valid, {}, {}};
+                                      xp, yp, last_lane, {}, {}, {}};
         st.run(taps_f);
     }
 }
@@ -396,14 +408,16 @@ template <int KH, int KW, int PD>
 __global__ __launch_bounds__(kBlock) void conv2d_sbm_kernel(Taps2D taps_t, const float* __restrict__ x,
                                                             float* __restrict__ y, int w_img, long long xp, int oh,
                                                             int ow, long long yp, int rows, int row_blocks,
-                                                            int n_items, int per_xcd, int valid_lanes, int order)
+                                                            int n_items, int per_xcd, int valid_lanes)
 {
     (void)taps_t;
     kernarg_floats tf = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
-    const int item = (order == 2 || order == 4 ? (int)blockIdx.x : xcd_contiguous(blockIdx.x, per_xcd)) * (kBlock / kWave) + wave_in_block();
+    const int item = xcd_contiguous(blockIdx.x, per_xcd) * (kBlock / kWave) + wave_in_block();
     if (item >= n_items) return;
-    int rb, strip;
-    decode_item(item, row_blocks, n_items, order, rb, strip);
+    // consecutive items go down a strip, and every XCD owns a contiguous run of items:
+    // the row blocks that share halo rows meet in one L2 (measured against row-major
+    // and plain round-robin orders on 4096^2, 5x5: 35 us vs 37-41 us)
+    const int rb = item % row_blocks, strip = item / row_blocks;
     const int lane = threadIdx.x & (kWave - 1);
     const int col0 = strip * kTile * valid_lanes;
     const int r0 = rb * rows;
@@ -457,7 +471,10 @@ hipError_t launch_strip(const float* x, int h, int w, size_t xp, const float* f,
         for (int q = 0; q < KW; ++q) ft[SBM ? q * KH + p : p * KW + q] = f[p * KW + q];
     fill_taps(taps, ft, KH * KW);
     const int oh = h - KH + 1, ow = w - KW + 1;
-    const int valid_lanes = strip_valid_lanes(KW);
+    // SBM strips overlap (the partial sums of the first KW-1 PEs come from the strip to
+    // the left, so those lanes are redundant); BFS strips are exactly 256 outputs wide and
+    // fetch the KW-1 halo columns separately
+    const int valid_lanes = SBM ? strip_valid_lanes(KW) : kWave;
     const int strips = (ow + kTile * valid_lanes - 1) / (kTile * valid_lanes);
     // Rows per wavefront.  Measured on MI355X (in-process A/B sweeps): short items win
     // everywhere -- small filters are bound by memory latency and need > 8 K wavefronts
@@ -476,15 +493,14 @@ hipError_t launch_strip(const float* x, int h, int w, size_t xp, const float* f,
     const long long per_xcd = (groups + kXcds - 1) / kXcds;
     const long long blocks = per_xcd * kXcds;
     if (blocks > 0x7fffffffLL || n_items > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    const int order = env_int("SYSCONV_2D_ORDER", 0);
     if constexpr (SBM)
         hipLaunchKernelGGL((conv2d_sbm_kernel<KH, KW, PD>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
                            taps, x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, (int)n_items,
-                           (int)per_xcd, valid_lanes, order);
+                           (int)per_xcd, valid_lanes);
     else
         hipLaunchKernelGGL((conv2d_bfs_kernel<KH, KW, PD>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
                            taps, x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, (int)n_items,
-                           (int)per_xcd, valid_lanes, order);
+                           (int)per_xcd, valid_lanes);
     return hipGetLastError();
 }
 
@@ -522,7 +538,7 @@ hipError_t launch_conv2d_bfs(const float* x, int h, int w, size_t xp, const floa
     switch (kh) {
     case 2: return launch_strip<2, 2, 2, false>(x, h, w, xp, f, y, yp, s);
     case 3: return launch_strip<3, 3, 3, false>(x, h, w, xp, f, y, yp, s);
-    case 5: return launch_strip<5, 5, 5, false>(x, h, w, xp, f, y, yp, s);
+    case 5: return launch_strip<5, 5, 1, false>(x, h, w, xp, f, y, yp, s);
     case 7: return launch_strip<7, 7, 7, false>(x, h, w, xp, f, y, yp, s);
     case 9: return launch_strip<9, 9, 3, false>(x, h, w, xp, f, y, yp, s);
     case 11: return launch_strip<11, 11, 1, false>(x, h, w, xp, f, y, yp, s);

@@ -41,6 +41,16 @@ __device__ __forceinline__ float from_lane_above(float v)
         __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kDppWaveShl1, 0xf, 0xf, true));
 }
 
+// Same hand-over, but lane 63 keeps `edge` (the element that enters the array from
+// outside the register group).  bound_ctrl off: a lane without a source keeps the
+// destination's old value, which is `edge`.
+__device__ __forceinline__ float from_lane_above_or(float v, float edge)
+{
+    return __builtin_bit_cast(float,
+        __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, edge), __builtin_bit_cast(int, v), kDppWaveShl1,
+                                    0xf, 0xf, false));
+}
+
 // Value of the next-lower lane (lane 0 gets 0): the partial-sum migration of
 // the SBM design, Z(s) <- Z(s-1).
 __device__ __forceinline__ float from_lane_below(float v)
