@@ -1,0 +1,140 @@
+"""GPU edge cases: degenerate shapes, very long / wide / tall inputs, non-finite data,
+call semantics (asynchrony, tap ownership)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_common import ORACLE_THREADS, TOL, dev, err1d, err2d, run1d, run2d
+from paper_2010_15884_amd import binding as B
+from paper_2010_15884_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+PROJ = ["FBS", "SBM", "BFS"]
+
+
+@pytest.mark.parametrize("proj", PROJ)
+def test_1d_very_long_signal(proj):
+    n, k = (1 << 27) + 3, 3
+    x, w = W.random_case(11, (n,), (k,))
+    y = run1d(x, w, proj)
+    ref = oracle.conv1d(x, w, ORACLE_THREADS)
+    scale = oracle.absdot1d(x, w, ORACLE_THREADS)
+    assert oracle.max_rel_err(y, ref, scale) <= TOL
+
+
+@pytest.mark.parametrize("proj", PROJ)
+def test_1d_nonfinite_inputs_stay_local(proj):
+    # an Inf or NaN may only reach the outputs whose window covers it: no tap-padding
+    # trick may multiply it by a zero weight elsewhere
+    for k in (1, 3, 4, 5, 8, 16, 17, 33, 64):
+        n = 3000
+        x, w = W.random_case(k, (n,), (k,))
+        w[np.abs(w) < 0.1] = 0.5                       # keep every tap clearly non-zero
+        bad = {700: np.inf, 1500: np.nan, n - 1: -np.inf, 0: np.inf}
+        for i, v in bad.items():
+            x[i] = v
+        y = run1d(x, w, proj)
+        m = n - k + 1
+        touched = np.zeros(m, bool)
+        for i in bad:
+            touched[max(0, i - k + 1):min(m, i + 1)] = True
+        assert np.isfinite(y[~touched]).all(), f"{proj} k={k}: non-finite value leaked"
+        assert (~np.isfinite(y[touched])).all(), f"{proj} k={k}: non-finite value lost"
+        xs = np.where(np.isfinite(x), x, 0).astype(np.float32)
+        ref = oracle.conv1d(xs, w)
+        scale = oracle.absdot1d(xs, w)
+        assert oracle.max_rel_err(y[~touched], ref[~touched], scale[~touched]) <= TOL
+
+
+def test_2d_nonfinite_inputs_stay_local():
+    for (kh, kw) in [(3, 3), (5, 5), (11, 11), (4, 6), (1, 9)]:
+        h, w_img = 70, 600
+        x, f = W.random_case(kh * 17 + kw, (h, w_img), (kh, kw), x_range=(0.0, 1.0))
+        f[np.abs(f) < 0.1] = 0.5
+        bad = [(0, 0), (33, 255), (34, 256), (h - 1, w_img - 1), (10, 511)]
+        for (r, c) in bad:
+            x[r, c] = np.inf
+        oh, ow = h - kh + 1, w_img - kw + 1
+        touched = np.zeros((oh, ow), bool)
+        for (r, c) in bad:
+            touched[max(0, r - kh + 1):min(oh, r + 1), max(0, c - kw + 1):min(ow, c + 1)] = True
+        for proj in PROJ:
+            if not B.sys_conv2d_has(proj, kh, kw):
+                continue
+            y = run2d(x, f, proj)
+            assert np.isfinite(y[~touched]).all(), f"{proj} {kh}x{kw}: non-finite value leaked"
+            assert (~np.isfinite(y[touched])).all(), f"{proj} {kh}x{kw}: non-finite value lost"
+
+
+@pytest.mark.parametrize("shape,kshape", [
+    ((12, 70001), (3, 3)), ((70001, 12), (3, 3)), ((5, 300000), (5, 5)), ((40000, 5), (5, 5)),
+    ((11, 5000), (11, 11)), ((3000, 11), (11, 11)), ((15, 15), (15, 15)), ((64, 257), (1, 1)),
+    ((9, 1000), (9, 1)), ((1000, 9), (1, 9)), ((2, 2), (2, 2)), ((1, 1), (1, 1)),
+])
+def test_2d_degenerate_and_extreme_shapes(shape, kshape):
+    x, f = W.random_case(shape[0] + shape[1], shape, kshape, x_range=(0.0, 1.0))
+    for proj in PROJ + ["AUTO"]:
+        if not B.sys_conv2d_has(proj, *kshape):
+            continue
+        y = run2d(x, f, proj)
+        assert y.shape == (shape[0] - kshape[0] + 1, shape[1] - kshape[1] + 1)
+        e = err2d(y, x, f)
+        assert e <= TOL, f"{proj} {kshape} on {shape}: {e}"
+
+
+def test_2d_odd_pitches():
+    # pitches that are not multiples of 4 elements: rows are only 4-byte aligned
+    for (kh, kw) in [(3, 3), (5, 5), (7, 2)]:
+        h, w_img = 50, 777
+        x, f = W.random_case(5 + kh, (h, w_img), (kh, kw), x_range=(0.0, 1.0))
+        oh, ow = h - kh + 1, w_img - kw + 1
+        for xp, yp in [(w_img + 1, ow + 3), (w_img + 2, ow + 1), (w_img + 3, ow + 2)]:
+            xbuf = torch.zeros((h, xp), dtype=torch.float32, device="cuda")
+            xbuf[:, :w_img] = dev(x)
+            for proj in PROJ:
+                if not B.sys_conv2d_has(proj, kh, kw):
+                    continue
+                ybuf = torch.full((oh, yp), -7.0, dtype=torch.float32, device="cuda")
+                B.sys_conv2d(xbuf[:, :w_img], f, ybuf[:, :ow], projection=proj)
+                torch.cuda.synchronize()
+                out = ybuf.cpu().numpy()
+                assert (out[:, ow:] == -7.0).all()
+                assert err2d(out[:, :ow], x, f) <= TOL, f"{proj} {kh}x{kw} pitches {xp},{yp}"
+
+
+def test_calls_are_ordered_on_their_stream_and_taps_are_copied_at_call_time():
+    # second call consumes the first call's output with no host synchronisation in between;
+    # the host tap arrays are overwritten right after each call returns
+    n, k1, k2 = 500000, 9, 16
+    x, w1 = W.random_case(21, (n,), (k1,))
+    _, w2 = W.random_case(22, (n,), (k2,))
+    w1c, w2c = w1.copy(), w2.copy()
+    dx = dev(x)
+    mid = torch.empty(n - k1 + 1, dtype=torch.float32, device="cuda")
+    out = torch.empty(n - k1 + 1 - k2 + 1, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    B.sys_conv1d(dx, w1c, mid, projection="FBS")
+    w1c[:] = 123.0
+    B.sys_conv1d(mid, w2c, out, projection="SBM")
+    w2c[:] = -55.0
+    torch.cuda.synchronize()
+    mid_h = mid.cpu().numpy()
+    assert err1d(mid_h, x, w1) <= TOL
+    assert err1d(out.cpu().numpy(), mid_h, w2) <= TOL
+
+
+def test_unsupported_requests_report_status_and_launch_nothing():
+    x = torch.zeros(1000, dtype=torch.float32, device="cuda")
+    y = torch.full((1000,), 3.0, dtype=torch.float32, device="cuda")
+    with pytest.raises(B.SysconvError) as ei:
+        B.sys_conv1d(x, np.ones(65, np.float32), y[:936], projection="FBS")
+    assert ei.value.status == B.SYS_ERR_UNSUPPORTED
+    img = torch.zeros((50, 50), dtype=torch.float32, device="cuda")
+    out = torch.full((47, 45), 3.0, dtype=torch.float32, device="cuda")
+    with pytest.raises(B.SysconvError) as ei:
+        B.sys_conv2d(img, np.ones((4, 6), np.float32), out, projection="BFS")
+    assert ei.value.status == B.SYS_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert float(y.min()) == 3.0 and float(out.min()) == 3.0
