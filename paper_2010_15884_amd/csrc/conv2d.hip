@@ -528,7 +528,7 @@ hipError_t launch_conv2d_fbs(const float* x, int h, int w, size_t xp, const floa
 
 bool has_conv2d_bfs(int kh, int kw)
 {
-    return (kh == kw) && (kh == 2 || kh == 3 || kh == 5 || kh == 7 || kh == 9 || kh == 11);
+    return kh == kw && kh >= 2 && kh <= 11;
 }
 
 hipError_t launch_conv2d_bfs(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
@@ -538,9 +538,13 @@ hipError_t launch_conv2d_bfs(const float* x, int h, int w, size_t xp, const floa
     switch (kh) {
     case 2: return launch_strip<2, 2, 2, false>(x, h, w, xp, f, y, yp, s);
     case 3: return launch_strip<3, 3, 3, false>(x, h, w, xp, f, y, yp, s);
+    case 4: return launch_strip<4, 4, 2, false>(x, h, w, xp, f, y, yp, s);
     case 5: return launch_strip<5, 5, 1, false>(x, h, w, xp, f, y, yp, s);
-    case 7: return launch_strip<7, 7, 7, false>(x, h, w, xp, f, y, yp, s);
-    case 9: return launch_strip<9, 9, 3, false>(x, h, w, xp, f, y, yp, s);
+    case 6: return launch_strip<6, 6, 2, false>(x, h, w, xp, f, y, yp, s);
+    case 7: return launch_strip<7, 7, 1, false>(x, h, w, xp, f, y, yp, s);
+    case 8: return launch_strip<8, 8, 2, false>(x, h, w, xp, f, y, yp, s);
+    case 9: return launch_strip<9, 9, 1, false>(x, h, w, xp, f, y, yp, s);
+    case 10: return launch_strip<10, 10, 1, false>(x, h, w, xp, f, y, yp, s);
     case 11: return launch_strip<11, 11, 1, false>(x, h, w, xp, f, y, yp, s);
     default: return hipErrorInvalidValue;
     }
@@ -555,9 +559,13 @@ hipError_t launch_conv2d_sbm(const float* x, int h, int w, size_t xp, const floa
     switch (kh) {
     case 2: return launch_strip<2, 2, 2, true>(x, h, w, xp, f, y, yp, s);
     case 3: return launch_strip<3, 3, 3, true>(x, h, w, xp, f, y, yp, s);
+    case 4: return launch_strip<4, 4, 3, true>(x, h, w, xp, f, y, yp, s);
     case 5: return launch_strip<5, 5, 3, true>(x, h, w, xp, f, y, yp, s);
+    case 6: return launch_strip<6, 6, 2, true>(x, h, w, xp, f, y, yp, s);
     case 7: return launch_strip<7, 7, 2, true>(x, h, w, xp, f, y, yp, s);
+    case 8: return launch_strip<8, 8, 2, true>(x, h, w, xp, f, y, yp, s);
     case 9: return launch_strip<9, 9, 2, true>(x, h, w, xp, f, y, yp, s);
+    case 10: return launch_strip<10, 10, 1, true>(x, h, w, xp, f, y, yp, s);
     case 11: return launch_strip<11, 11, 1, true>(x, h, w, xp, f, y, yp, s);
     default: return hipErrorInvalidValue;
     }

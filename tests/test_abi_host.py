@@ -106,7 +106,7 @@ def test_conv2d_has():
     assert B.sys_conv2d_has("FBS", 15, 15) and B.sys_conv2d_has("AUTO", 1, 9)
     assert not B.sys_conv2d_has("FBS", 16, 3)
     assert B.sys_conv2d_has("BFS", 3, 3) and B.sys_conv2d_has("BFS", 5, 5) and B.sys_conv2d_has("BFS", 11, 11)
-    assert not B.sys_conv2d_has("BFS", 4, 5)
+    assert not B.sys_conv2d_has("BFS", 4, 5) and not B.sys_conv2d_has("SBM", 12, 12)
     assert not B.sys_conv2d_has(42, 3, 3)
 
 

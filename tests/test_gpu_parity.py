@@ -92,7 +92,7 @@ def test_conv1d_adjacent_buffers_are_accepted():
 
 
 # ------------------------------------------------------------------- 2-D
-SHAPES_2D = [(1, 1), (1, 5), (5, 1), (2, 2), (3, 3), (5, 5), (7, 7), (9, 9), (11, 11), (15, 15), (3, 8), (8, 3), (4, 13)]
+SHAPES_2D = [(1, 1), (1, 5), (5, 1), (2, 2), (3, 3), (4, 4), (5, 5), (6, 6), (7, 7), (8, 8), (9, 9), (10, 10), (11, 11), (12, 12), (15, 15), (3, 8), (8, 3), (4, 13)]
 
 
 def _images(kh, kw):
