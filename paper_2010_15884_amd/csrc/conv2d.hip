@@ -481,8 +481,10 @@ hipError_t launch_strip(const float* x, int h, int w, size_t xp, const float* f,
     // in flight (4096^2, 5x5, SBM: 27 us with 4 rows, 30 us with 16), large ones are
     // bound by the VALUs and lose to the tail of a coarse decomposition (8192^2, 11x11,
     // SBM: 246 us with 8 rows, 266 us with 24, 317 us with 64).  BFS pays KH(KH-1)/2
-    // skipped filter-row blocks per item, so its items are a little taller.  The halo
-    // rows that short items re-read come mostly from cache.
+    // skipped filter-row blocks per item, so its items are a little taller.  The price
+    // is halo traffic: an item re-reads KH-1 input rows; for 5x5 most of those re-reads
+    // hit in cache (HBM reads 1.14x the image), for 11x11 they do not (2.1x) -- harmless
+    // there, the kernel is bound by the VALUs and moves 3.3 TB/s.
     const int rows_env = env_int("SYSCONV_BFS_ROWS", 0);
     int rows = rows_env;
     if (rows <= 0) rows = SBM ? (KH <= 5 ? 4 : 8) : (KH <= 5 ? 6 : 16);
