@@ -48,6 +48,10 @@ int sys_conv1d(const float* d_x, size_t n, const float* h_w, int k, float* d_y, 
 
     switch (projection) {
     case SYS_PROJ_AUTO:
+        // long filters are bound by the VALUs, where BFS issues the fewest instructions
+        // (n = 2^26: k = 48: 122 us against 158 us for FBS; below k = 33 all sit on the copy rate)
+        if (k >= 36) return hip_status(sysconv::launch_conv1d_bfs(d_x, n, h_w, k, d_y, stream));
+        return hip_status(sysconv::launch_conv1d_fbs(d_x, n, h_w, k, d_y, stream));
     case SYS_PROJ_FBS: return hip_status(sysconv::launch_conv1d_fbs(d_x, n, h_w, k, d_y, stream));
     case SYS_PROJ_SBM: return hip_status(sysconv::launch_conv1d_sbm(d_x, n, h_w, k, d_y, stream));
     case SYS_PROJ_BFS:
@@ -96,9 +100,10 @@ int sys_conv2d(const float* d_x, int h, int w, size_t x_pitch, const float* h_f,
     if (ranges_overlap(d_x, x_bytes, d_y, y_bytes)) return SYS_ERR_ALIAS;
 
     int proj = projection;
-    // measured order on MI355X: SBM >= BFS > FBS wherever the strip kernels are built
+    // measured on MI355X: BFS (block form) wins up to 7x7, SBM from 8x8 on, FBS serves the rest
     if (proj == SYS_PROJ_AUTO)
-        proj = sysconv::has_conv2d_sbm(kh, kw) ? SYS_PROJ_SBM
+        proj = (kh <= 7 && sysconv::has_conv2d_bfs(kh, kw)) ? SYS_PROJ_BFS
+             : sysconv::has_conv2d_sbm(kh, kw) ? SYS_PROJ_SBM
              : sysconv::has_conv2d_bfs(kh, kw) ? SYS_PROJ_BFS : SYS_PROJ_FBS;
     switch (proj) {
     case SYS_PROJ_FBS:

@@ -9,7 +9,6 @@
 #include "launch.h"
 #include "systolic.h"
 
-#include <cstdlib>
 
 namespace sysconv {
 namespace {
@@ -396,9 +395,7 @@ hipError_t launch_1d_bfs(const float* x, size_t n, const float* w, int k, float*
 #endif
 int group_valid_lanes(int k)
 {
-    int v = kWave - halo_lanes(k);
-    static const int forced = [] { const char* e = std::getenv("SYSCONV_1D_VALID"); return e ? std::atoi(e) : 0; }();
-    if (forced > 0 && forced <= v) return forced;
+    const int v = kWave - halo_lanes(k);
     return v - v % SYSCONV_1D_LANE_ALIGN;
 }
 

@@ -7,7 +7,6 @@
 #include "launch.h"
 #include "systolic.h"
 
-#include <cstdlib>
 
 namespace sysconv {
 namespace {
@@ -437,23 +436,113 @@ __global__ __launch_bounds__(kBlock) void conv2d_sbm_kernel(Taps2D taps_t, const
     }
 }
 
-int env_int(const char* name, int fallback)
+// ----------------------------------------------------- BFS 2-D, block form ---
+// The same BFS-along-rows x FBS-along-columns array as BfsStrip, for filters
+// small enough to be bound by memory: a wavefront takes a block of ROWS output
+// rows of one 256-column strip, issues the loads of ALL ROWS+KH-1 input rows up
+// front, and then runs in straight-line code (no row loop, every validity test
+// decided at compile time).  With every load in flight at once a wavefront pays
+// one memory latency per block, and the compiler's wait counts are exact.
+// The KW-1 halo columns right of the strip are the same for all lanes, so they
+// are fetched with uniform (scalar) loads and enter the array in lane 63.
+template <int KH, int KW, int ROWS, bool EDGE>
+__device__ __forceinline__ void bfs_block_rows(kernarg_floats taps_f, const float* __restrict__ xrow,
+                                               float* __restrict__ yrow, int col0, int lane, int w_img,
+                                               long long xp, int ow, long long yp, int rows_out)
 {
-    const char* v = std::getenv(name);
-    if (!v || !*v) return fallback;
-    const int x = std::atoi(v);
-    return x > 0 ? x : fallback;
+    constexpr int NIN = ROWS + KH - 1;
+    constexpr int NH = (KW + 2) / 4;                                       // halo float4s
+    const int col = col0 + kTile * lane;
+    const int rows_in = rows_out + KH - 1;
+
+    float v[NIN][4];
+    float h[NIN][NH][4];
+#pragma unroll
+    for (int rho = 0; rho < NIN; ++rho) {
+        // rows past the end of the block repeat its last row; they only feed output rows
+        // that are not stored
+        const float* p = xrow + (long long)min(rho, rows_in - 1) * xp;
+        if (EDGE) {
+            load4_guarded<false>(p, col, w_img, v[rho]);
+#pragma unroll
+            for (int j = 0; j < NH; ++j) load4_guarded<false>(p, col0 + kStrip + 4 * j, w_img, h[rho][j]);
+        } else {
+            const f4u t = *reinterpret_cast<const f4u*>(p + col);
+            v[rho][0] = t.x; v[rho][1] = t.y; v[rho][2] = t.z; v[rho][3] = t.w;
+            const float* hp = p + col0 + kStrip;                           // wave-uniform address
+#pragma unroll
+            for (int j = 0; j < NH; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) h[rho][j][i] = hp[4 * j + i];
+        }
+    }
+
+    float acc[ROWS][4];
+#pragma unroll
+    for (int rho = 0; rho < NIN; ++rho) {
+        float win[KW + 3];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) win[i] = v[rho][i];
+#pragma unroll
+        for (int m = 4; m < KW + 3; ++m)
+            win[m] = from_lane_above_or(win[m - 4], h[rho][(m - 4) / 4][(m - 4) % 4]);
+#pragma unroll
+        for (int p = 0; p < KH; ++p) {
+            const int r = rho - p;                                         // compile-time
+            if (r < 0 || r >= ROWS) continue;
+#pragma unroll
+            for (int q = 0; q < KW; ++q) {
+                const float wv = taps_f[p * KW + q];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (p == 0 && q == 0) acc[r][i] = wv * win[i];
+                    else acc[r][i] = __builtin_fmaf(wv, win[q + i], acc[r][i]);
+                }
+            }
+        }
+        const int done = rho - (KH - 1);
+        if (done >= 0 && done < rows_out) {
+            float* yr = yrow + (long long)done * yp;
+            if (EDGE) {
+                store4_guarded(yr, col, ow, acc[done]);
+            } else {
+                f4u t;
+                t.x = acc[done][0]; t.y = acc[done][1]; t.z = acc[done][2]; t.w = acc[done][3];
+                if (SYSCONV_NONTEMPORAL_STORE) __builtin_nontemporal_store(t, reinterpret_cast<f4u*>(yr + col));
+                else *reinterpret_cast<f4u*>(yr + col) = t;
+            }
+        }
+    }
 }
 
-// Lanes of a strip that keep their results: 64 - halo_lanes(kw).  (Rounding the
+template <int KH, int KW, int ROWS>
+__global__ __launch_bounds__(kBlock) void conv2d_bfs_block_kernel(Taps2D taps, const float* __restrict__ x,
+                                                                  float* __restrict__ y, int w_img, long long xp,
+                                                                  int oh, int ow, long long yp, int row_blocks,
+                                                                  int n_items, int per_xcd)
+{
+    (void)taps;
+    kernarg_floats taps_f = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
+    const int item = xcd_contiguous(blockIdx.x, per_xcd) * (kBlock / kWave) + wave_in_block();
+    if (item >= n_items) return;                                           // uniform per wavefront
+    const int rb = item % row_blocks, strip = item / row_blocks;           // consecutive items go down a strip
+    const int lane = threadIdx.x & (kWave - 1);
+    const int col0 = strip * kStrip;
+    const int r0 = rb * ROWS;
+    const int rows_out = min(ROWS, oh - r0);
+    const float* xrow = x + (long long)r0 * xp;
+    float* yrow = y + (long long)r0 * yp;
+    constexpr int halo_cols = kTile * ((KW + 2) / 4);
+    if (col0 + kStrip + halo_cols <= w_img)
+        bfs_block_rows<KH, KW, ROWS, false>(taps_f, xrow, yrow, col0, lane, w_img, xp, ow, yp, rows_out);
+    else
+        bfs_block_rows<KH, KW, ROWS, true>(taps_f, xrow, yrow, col0, lane, w_img, xp, ow, yp, rows_out);
+}
+
+// Lanes of an SBM strip that keep their results: 64 - halo_lanes(kw).  (Rounding the
 // strip width down to whole cache lines was measured and does not pay in 2-D:
 // 4096^2, 5x5: 28.1 us with 63 lanes, 29.0 with 60, 29.3 with 56.)
-int strip_valid_lanes(int kw)
-{
-    const int v = kWave - halo_lanes(kw);
-    const int forced = env_int("SYSCONV_2D_VALID", 0);
-    return (forced > 0 && forced <= v) ? forced : v;
-}
+int strip_valid_lanes(int kw) { return kWave - halo_lanes(kw); }
 
 void fill_taps(Taps2D& taps, const float* f, int n)
 {
@@ -485,9 +574,7 @@ hipError_t launch_strip(const float* x, int h, int w, size_t xp, const float* f,
     // is halo traffic: an item re-reads KH-1 input rows; for 5x5 most of those re-reads
     // hit in cache (HBM reads 1.14x the image), for 11x11 they do not (2.1x) -- harmless
     // there, the kernel is bound by the VALUs and moves 3.3 TB/s.
-    const int rows_env = env_int("SYSCONV_BFS_ROWS", 0);
-    int rows = rows_env;
-    if (rows <= 0) rows = SBM ? (KH <= 5 ? 4 : 8) : (KH <= 5 ? 6 : 16);
+    int rows = SBM ? (KH <= 5 ? 4 : 8) : (KH <= 5 ? 6 : 16);
     if (rows > oh) rows = oh;
     const int row_blocks = (oh + rows - 1) / rows;
     const long long n_items = (long long)row_blocks * strips;
@@ -528,6 +615,26 @@ hipError_t launch_conv2d_fbs(const float* x, int h, int w, size_t xp, const floa
     return hipGetLastError();
 }
 
+template <int KH, int KW, int ROWS>
+hipError_t launch_bfs_block(const float* x, int h, int w, size_t xp, const float* f, float* y, size_t yp,
+                            hipStream_t s)
+{
+    Taps2D taps;
+    fill_taps(taps, f, KH * KW);
+    const int oh = h - KH + 1, ow = w - KW + 1;
+    const int strips = (ow + kStrip - 1) / kStrip;
+    const int row_blocks = (oh + ROWS - 1) / ROWS;
+    const long long n_items = (long long)row_blocks * strips;
+    const long long groups = (n_items + (kBlock / kWave) - 1) / (kBlock / kWave);
+    const long long per_xcd = (groups + kXcds - 1) / kXcds;
+    const long long blocks = per_xcd * kXcds;
+    if (blocks > 0x7fffffffLL || n_items > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((conv2d_bfs_block_kernel<KH, KW, ROWS>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
+                       taps, x, y, w, (long long)xp, oh, ow, (long long)yp, row_blocks, (int)n_items,
+                       (int)per_xcd);
+    return hipGetLastError();
+}
+
 bool has_conv2d_bfs(int kh, int kw)
 {
     return kh == kw && kh >= 2 && kh <= 11;
@@ -538,12 +645,16 @@ hipError_t launch_conv2d_bfs(const float* x, int h, int w, size_t xp, const floa
 {
     if (kh != kw) return hipErrorInvalidValue;
     switch (kh) {
-    case 2: return launch_strip<2, 2, 2, false>(x, h, w, xp, f, y, yp, s);
-    case 3: return launch_strip<3, 3, 3, false>(x, h, w, xp, f, y, yp, s);
-    case 4: return launch_strip<4, 4, 2, false>(x, h, w, xp, f, y, yp, s);
-    case 5: return launch_strip<5, 5, 1, false>(x, h, w, xp, f, y, yp, s);
-    case 6: return launch_strip<6, 6, 2, false>(x, h, w, xp, f, y, yp, s);
-    case 7: return launch_strip<7, 7, 1, false>(x, h, w, xp, f, y, yp, s);
+    // Filters up to 7x7 are bound by memory on large images and run the block form (block
+    // heights from a sweep on 4096^2, cold data: 2x2..5x5: 29 us with 2 rows against 31-35 us
+    // for taller blocks or the strip walk; 6x6: 35 us with 3; 7x7: 38 us with 4); from 8x8 on
+    // the VALUs bound the kernel and the strip walk with its register ring is faster.
+    case 2: return launch_bfs_block<2, 2, 2>(x, h, w, xp, f, y, yp, s);
+    case 3: return launch_bfs_block<3, 3, 2>(x, h, w, xp, f, y, yp, s);
+    case 4: return launch_bfs_block<4, 4, 2>(x, h, w, xp, f, y, yp, s);
+    case 5: return launch_bfs_block<5, 5, 2>(x, h, w, xp, f, y, yp, s);
+    case 6: return launch_bfs_block<6, 6, 3>(x, h, w, xp, f, y, yp, s);
+    case 7: return launch_bfs_block<7, 7, 4>(x, h, w, xp, f, y, yp, s);
     case 8: return launch_strip<8, 8, 2, false>(x, h, w, xp, f, y, yp, s);
     case 9: return launch_strip<9, 9, 1, false>(x, h, w, xp, f, y, yp, s);
     case 10: return launch_strip<10, 10, 1, false>(x, h, w, xp, f, y, yp, s);
