@@ -138,3 +138,25 @@ def test_unsupported_requests_report_status_and_launch_nothing():
     assert ei.value.status == B.SYS_ERR_UNSUPPORTED
     torch.cuda.synchronize()
     assert float(y.min()) == 3.0 and float(out.min()) == 3.0
+
+
+def test_2d_calls_chain_on_a_stream_without_host_sync():
+    # the second call reads what the first wrote (its halo columns travel through the
+    # scalar cache): back-to-back launches must see fresh data
+    h, w_img = 300, 1100
+    x, f1 = W.random_case(31, (h, w_img), (5, 5), x_range=(0.0, 1.0))
+    _, f2 = W.random_case(32, (h, w_img), (3, 3), x_range=(0.0, 1.0))
+    dx = dev(x)
+    mid = torch.zeros((h - 4, w_img - 4), dtype=torch.float32, device="cuda")
+    out = torch.zeros((h - 6, w_img - 6), dtype=torch.float32, device="cuda")
+    for rep in range(3):
+        dx.mul_(1.0 + 0.25 * rep)                      # change the input between rounds
+        torch.cuda.synchronize()
+        xh = dx.cpu().numpy()
+        for proj in ("BFS", "SBM", "FBS"):
+            B.sys_conv2d(dx, f1, mid, projection=proj)
+            B.sys_conv2d(mid, f2, out, projection=proj)
+            torch.cuda.synchronize()
+            mid_h = mid.cpu().numpy()
+            assert err2d(mid_h, xh, f1) <= TOL, f"{proj} round {rep} first call"
+            assert err2d(out.cpu().numpy(), mid_h, f2) <= TOL, f"{proj} round {rep} second call"
