@@ -48,5 +48,20 @@ def build(verbose: bool = True, lib: str = LIB) -> str:
     return lib
 
 
+def build_c_demo(verbose: bool = True) -> str:
+    """Compile examples/c_abi_demo.c with gcc as C99 against the built library: the
+    header is plain C and the ABI needs nothing but the HIP runtime."""
+    src = os.path.join(ROOT, "examples", "c_abi_demo.c")
+    exe = os.path.join(ROOT, "examples", "c_abi_demo")
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
+           "-I", os.path.join(ROOT, "include"), src, "-L", HERE, "-lsysconv", "-L/opt/rocm/lib", "-lamdhip64",
+           "-lm", "-Wl,-rpath," + HERE, "-Wl,-rpath,/opt/rocm/lib", "-o", exe]
+    subprocess.run(cmd, check=True)
+    if verbose:
+        print(f"built {exe}")
+    return exe
+
+
 if __name__ == "__main__":
     build()
+    build_c_demo()
