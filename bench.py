@@ -198,7 +198,7 @@ def main() -> int:
             _, c_mean, _ = time_launches(copy_launch, steps, 3)
             copy_gbs = 8 * n_copy / c_mean / 1e9
             del srcs, dsts
-            for proj in ("FBS", "SBM", "BFS"):
+            for proj in ("FBS", "SBM", "BFS", "BSM", "FSM", "FFS"):
                 has = B.sys_conv1d_has(proj, w2.k_shape[0]) if w2.ndim == 1 else B.sys_conv2d_has(proj, *w2.k_shape)
                 if not has:
                     continue

@@ -29,6 +29,12 @@
  *        it while the weights move past (Table 2, row 2 left).  Here the PE
  *        array runs along the per-lane registers (1-D: consecutive outputs of
  *        one lane; 2-D: consecutive output rows of one lane).
+ *   BSM, FSM, FFS (1-D only)  the remaining designs of Table 2, one PE per lane:
+ *        BSM and FSM arrays are k lanes long (PE = tap; weights stay; partial sums
+ *        move up resp. down; inputs are broadcast resp. move at half speed), FFS
+ *        arrays are 16 PEs long (PE = output; inputs and weights both move).  The
+ *        paper measures them as inferior; they are provided to reproduce that
+ *        ranking, and run several times slower than FBS / SBM / BFS.
  *
  * Conventions common to every entry point
  *   - d_* pointers are DEVICE memory on the current HIP device; h_* pointers
@@ -73,7 +79,10 @@ typedef enum {
     SYS_PROJ_AUTO = 0,        /* the fastest projection available for the size       */
     SYS_PROJ_FBS = 1,
     SYS_PROJ_BFS = 2,
-    SYS_PROJ_SBM = 3
+    SYS_PROJ_SBM = 3,
+    SYS_PROJ_BSM = 4,         /* 1-D only */
+    SYS_PROJ_FSM = 5,         /* 1-D only */
+    SYS_PROJ_FFS = 6          /* 1-D only */
 } sys_projection_t;
 
 /* Limits.  Larger filters return SYS_ERR_UNSUPPORTED. */
@@ -85,8 +94,8 @@ typedef enum {
  *   d_x   device, n floats (read only)
  *   h_w   host, k floats, 1 <= k <= min(n, SYS_MAX_K1D)
  *   d_y   device, n-k+1 floats (written; nothing else is touched)
- *   projection  a sys_projection_t; AUTO, FBS and SBM accept every k in range;
- *         sys_conv1d_has tells whether BFS is built for a given k
+ *   projection  a sys_projection_t; every projection accepts every k in range
+ *         (sys_conv1d_has reports it)
  */
 int sys_conv1d(const float *d_x, size_t n,
                const float *h_w, int k,
@@ -101,9 +110,9 @@ int sys_conv1d(const float *d_x, size_t n,
  *   h_f      host, kh*kw floats row-major, 1 <= kh <= min(h, SYS_MAX_K2D), same for kw / w
  *   d_y      device, h-kh+1 rows of w-kw+1 floats, row stride y_pitch elements
  *            (>= w-kw+1); elements between rows are left untouched
- *   projection  FBS accepts every filter in range; BFS and SBM are built for a
- *            fixed list of filter sizes (sys_conv2d_has) and return
- *            SYS_ERR_UNSUPPORTED otherwise; AUTO never does.
+ *   projection  AUTO and FBS accept every filter in range; BFS and SBM are built
+ *            for a fixed list of filter sizes (sys_conv2d_has) and return
+ *            SYS_ERR_UNSUPPORTED otherwise; BSM, FSM and FFS are 1-D only.
  */
 int sys_conv2d(const float *d_x, int h, int w, size_t x_pitch,
                const float *h_f, int kh, int kw,

@@ -26,7 +26,7 @@ bool ranges_overlap(const void* a, size_t a_bytes, const void* b, size_t b_bytes
 
 bool known_projection(int p)
 {
-    return p == SYS_PROJ_AUTO || p == SYS_PROJ_FBS || p == SYS_PROJ_BFS || p == SYS_PROJ_SBM;
+    return p >= SYS_PROJ_AUTO && p <= SYS_PROJ_FFS;
 }
 
 bool misaligned(const void* p) { return ((uintptr_t)p & 3u) != 0; }
@@ -57,6 +57,9 @@ int sys_conv1d(const float* d_x, size_t n, const float* h_w, int k, float* d_y, 
     case SYS_PROJ_BFS:
         if (!sysconv::has_conv1d_bfs(k)) return SYS_ERR_UNSUPPORTED;
         return hip_status(sysconv::launch_conv1d_bfs(d_x, n, h_w, k, d_y, stream));
+    case SYS_PROJ_BSM: return hip_status(sysconv::launch_conv1d_bsm(d_x, n, h_w, k, d_y, stream));
+    case SYS_PROJ_FSM: return hip_status(sysconv::launch_conv1d_fsm(d_x, n, h_w, k, d_y, stream));
+    case SYS_PROJ_FFS: return hip_status(sysconv::launch_conv1d_ffs(d_x, n, h_w, k, d_y, stream));
     default: return SYS_ERR_UNSUPPORTED;
     }
 }
@@ -67,7 +70,10 @@ int sys_conv1d_has(int projection, int k)
     switch (projection) {
     case SYS_PROJ_AUTO:
     case SYS_PROJ_FBS:
-    case SYS_PROJ_SBM: return 1;
+    case SYS_PROJ_SBM:
+    case SYS_PROJ_BSM:
+    case SYS_PROJ_FSM:
+    case SYS_PROJ_FFS: return 1;
     case SYS_PROJ_BFS: return sysconv::has_conv1d_bfs(k) ? 1 : 0;
     default: return 0;
     }
@@ -114,7 +120,7 @@ int sys_conv2d(const float* d_x, int h, int w, size_t x_pitch, const float* h_f,
     case SYS_PROJ_SBM:
         if (!sysconv::has_conv2d_sbm(kh, kw)) return SYS_ERR_UNSUPPORTED;
         return hip_status(sysconv::launch_conv2d_sbm(d_x, h, w, x_pitch, h_f, kh, kw, d_y, y_pitch, stream));
-    default: return SYS_ERR_UNSUPPORTED;
+    default: return SYS_ERR_UNSUPPORTED;                               // BSM, FSM, FFS are 1-D only
     }
 }
 
@@ -147,6 +153,9 @@ const char* sys_projection_name(int projection)
     case SYS_PROJ_FBS: return "FBS";
     case SYS_PROJ_BFS: return "BFS";
     case SYS_PROJ_SBM: return "SBM";
+    case SYS_PROJ_BSM: return "BSM";
+    case SYS_PROJ_FSM: return "FSM";
+    case SYS_PROJ_FFS: return "FFS";
     default: return "?";
     }
 }

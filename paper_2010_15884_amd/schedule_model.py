@@ -12,8 +12,8 @@ where #lanes is the length of the *virtual* PE vector (the extent of P.z) and
 #time steps the extent of s^T.z.  With 16 outputs and 5 taps this reproduces
 the paper's Table 4.
 
-``wave64`` evaluates the same two figures for the way the HIP kernels lay a
-design over a 64-lane wavefront with a 4-float tile per lane.
+``wave64`` evaluates the same two figures for the way the HIP kernels lay each
+design over a 64-lane wavefront.
 
 Host-side bookkeeping only: no convolution arithmetic lives here.
 """
@@ -95,21 +95,36 @@ def model(design: str, n_out: int = 16, n_taps: int = 5) -> Dict[str, float]:
 
 
 def wave64(design: str, n_taps: int, groups: int = 4, tile: int = 4, lanes: int = 64) -> Dict[str, float]:
-    """The same model for a wavefront that streams ``groups`` register groups of
-    ``lanes`` x ``tile`` consecutive elements (the HIP kernels' layout).
+    """The same model for the way the HIP kernels lay each design over a 64-lane
+    wavefront.  "lanes" counts PE slots, "steps" time steps, utilisation is the share
+    of PE-steps that are useful multiply-adds.
 
-    FBS: every (lane, tile slot) is a PE that owns one output; the array runs
-         n_taps steps per group and every PE-step is a useful multiply-add.
-    SBM: the PE vector also carries the n_taps-1 slots the partial sums migrate
-         through, so a chunk of lanes*tile*groups inputs yields n_taps-1 fewer
-         outputs (the paper's vector length Q+CCC-1).
+    FBS: a wavefront streams ``groups`` register groups of ``lanes`` x ``tile`` PEs; every
+         PE owns one output and runs n_taps steps, all useful.
+    SBM: the PE vector also carries the n_taps-1 slots the partial sums migrate through,
+         so a chunk yields n_taps-1 fewer outputs (the paper's vector length Q+CCC-1).
+    BFS: every lane is a ``tile``-PE array; an array sees n_taps+tile-1 inputs, and a PE
+         is busy for n_taps of them (idle PE-steps are not issued on the GPU: the PEs of
+         a lane share one ALU).
+    BSM, FSM: arrays are n_taps lanes long, lanes // n_taps of them per wavefront, each
+         streaming a segment of ~1024 / arrays outputs with one fill / drain of n_taps-1.
+    FFS: arrays of 16 PEs (the paper's size), 2*15 + n_taps steps for 16 outputs each.
     """
-    n_pe = lanes * tile * groups
-    if design == "FBS":
-        outs, steps = n_pe, n_taps
-    elif design == "SBM":
-        outs, steps = n_pe - (n_taps - 1), n_taps
+    if design in ("FBS", "SBM"):
+        n_pe = lanes * tile * groups
+        outs = n_pe if design == "FBS" else n_pe - (n_taps - 1)
+        steps = n_taps
+    elif design == "BFS":
+        n_pe = lanes * tile * groups
+        outs, steps = n_pe, n_taps + tile - 1
+    elif design in ("BSM", "FSM"):
+        arrays = lanes // n_taps
+        seg = (1024 // arrays) & ~3
+        n_pe, outs, steps = lanes, arrays * seg, seg + n_taps - 1
+    elif design == "FFS":
+        width = 16
+        n_pe, outs, steps = lanes, lanes, 2 * (width - 1) + n_taps
     else:
-        raise ValueError("wave64 model is written for the wave-wide designs FBS and SBM")
+        raise ValueError(design)
     return {"lanes": n_pe, "steps": steps, "outturn": outs / steps,
             "utilisation": outs * n_taps / (n_pe * steps)}

@@ -33,7 +33,7 @@ def test_strings_and_version():
     for s in range(1, 6):
         assert B.status_string(s) not in ("ok", "unknown status")
     assert B.status_string(99) == "unknown status"
-    assert [B.projection_name(p) for p in range(4)] == ["AUTO", "FBS", "BFS", "SBM"]
+    assert [B.projection_name(p) for p in range(7)] == ["AUTO", "FBS", "BFS", "SBM", "BSM", "FSM", "FFS"]
     assert B.projection_name(17) == "?"
 
 
@@ -82,6 +82,7 @@ def test_conv1d_validation(args, want):
     ((X, 100, 100, 100, "f", 16, 3, Y, 98, 1), B.SYS_ERR_UNSUPPORTED),
     ((X, 100, 100, 100, "f", 3, 16, Y, 98, 1), B.SYS_ERR_UNSUPPORTED),
     ((X, 100, 100, 100, "f", 3, 3, Y, 98, 9), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, 100, 100, "f", 3, 3, Y, 98, B.SYS_PROJ_BSM), B.SYS_ERR_UNSUPPORTED),
     ((X, 100, 100, 100, "f", 4, 3, Y, 98, B.SYS_PROJ_BFS), B.SYS_ERR_UNSUPPORTED),
     ((X + 1, 100, 100, 100, "f", 3, 3, Y, 98, 1), B.SYS_ERR_UNSUPPORTED),
     ((X, 100, 100, 100, "f", 3, 3, X + 4 * 5000, 98, 1), B.SYS_ERR_ALIAS),

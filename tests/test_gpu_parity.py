@@ -10,7 +10,7 @@ from paper_2010_15884_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
 
-PROJ_1D = ["FBS", "SBM", "BFS"]
+PROJ_1D = ["FBS", "SBM", "BFS", "BSM", "FSM", "FFS"]
 K_1D = [1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 13, 16, 17, 31, 32, 33, 63, 64]
 
 

@@ -18,7 +18,7 @@ def test_1d_workloads(name):
     x, w = W.make(wl)
     ref = oracle.conv1d(x, w, ORACLE_THREADS)
     scale = oracle.absdot1d(x, w, ORACLE_THREADS)
-    for proj in ("FBS", "SBM", "BFS"):
+    for proj in ("FBS", "SBM", "BFS", "BSM", "FSM", "FFS"):
         if not B.sys_conv1d_has(proj, len(w)):
             continue
         y = run1d(x, w, proj)

@@ -129,3 +129,11 @@ def test_wave64_model():
     assert fbs["utilisation"] == 1.0 and fbs["steps"] == 16
     sbm = sm.wave64("SBM", 16)
     assert sbm["utilisation"] == pytest.approx((1024 - 15) / 1024)
+    # K-lane arrays: 12 arrays of 5 lanes, segments of 84 outputs, 88 steps
+    bsm = sm.wave64("BSM", 5)
+    assert (bsm["steps"], bsm["outturn"]) == (88, pytest.approx(12 * 84 / 88))
+    assert bsm["utilisation"] == pytest.approx(12 * 84 * 5 / (64 * 88))
+    assert sm.wave64("FSM", 5) == bsm
+    # FFS with 16-PE arrays has exactly the paper's Table 4 utilisation at K = 5: 16*5/(16*35)
+    assert sm.wave64("FFS", 5)["utilisation"] == pytest.approx(sm.model("FFS", 16, 5)["utilisation"])
+    assert sm.wave64("BFS", 5)["utilisation"] == pytest.approx(5 / 8)
