@@ -50,6 +50,9 @@ def _parse():
     ap.add_argument("--projection", default="AUTO")
     ap.add_argument("--no-extras", action="store_true", help="skip the other workloads / projections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--design-space", action="store_true",
+                    help="only time the six 1-D designs of the paper's Table 2 at n=2^26 for k in {2, 5, 16} "
+                         "(the paper's Table 3 uses k = 2 and 5) and print that table as JSON")
     return ap.parse_args()
 
 
@@ -124,6 +127,36 @@ def main() -> int:
         wall = time.perf_counter() - t0
         per = [a.elapsed_time(b) * 1e-3 for a, b in evs]
         return wall, sum(per) / len(per), sorted(per)[len(per) // 2]
+
+    if args.design_space:
+        from paper_2010_15884_amd import schedule_model as sm
+        paper_rel = {"SBM": (157, 147), "BSM": (67, 49), "FSM": (56, 39), "BFS": (56, 48), "FFS": (33, 30),
+                     "FBS": (159, 157)}                    # Table 3: % of the hardware sampler at k = 2, 5
+        wl = W.WORKLOADS[HEADLINE]
+        x_host, _ = W.make(wl)
+        rows = []
+        for k in (2, 5, 16):
+            taps = W.uniform_f32(np.random.default_rng(15884 + k), -1.0, 1.0, (k,))
+            wk = W.Workload(f"conv1d_64m_k{k}", 1, wl.x_shape, (k,), wl.x_range, wl.w_range, wl.seed)
+            t_fbs = None
+            for proj in ("FBS", "SBM", "BFS", "BSM", "FSM", "FFS"):
+                ln, kp = make_launcher(wk, proj, x_host, taps)
+                _, k_mean, _ = time_launches(ln, 10, 2)
+                del ln, kp
+                t_fbs = k_mean if proj == "FBS" else t_fbs
+                row = {"k": k, "design": proj, "kernel_us": round(k_mean * 1e6, 1),
+                       "GB/s": round(wk.algorithmic_bytes / k_mean / 1e9, 1),
+                       "Gtap/s": round(wk.n_taps / k_mean / 1e9, 1),
+                       "relative_to_FBS": round(t_fbs / k_mean, 3),
+                       "model_utilisation_wave64": round(sm.wave64(proj, k)["utilisation"], 3)}
+                if k in (2, 5):
+                    p = paper_rel[proj][0 if k == 2 else 1]
+                    row["paper_relative_to_FBS"] = round(p / paper_rel["FBS"][0 if k == 2 else 1], 3)
+                rows.append(row)
+        print(json.dumps({"design_space_1d": rows, "n": wl.x_shape[0], "data": "synthetic",
+                          "note": "paper column: Table 3 (Intel GEN9.5, relative to its hardware sampler), "
+                                  "rescaled to FBS = 1; context, not a target"}))
+        return 0
 
     # ------------------------------------------------------------ headline step
     wl = W.WORKLOADS[HEADLINE]

@@ -28,8 +28,10 @@ namespace {
 typedef const float __attribute__((address_space(4)))* kernarg_floats;
 
 constexpr int kChunk = 1024;                                  // outputs per wavefront (at most)
-constexpr int kInFloats = kChunk + kMaxK1D + 4;               // chunk + k - 1, rounded up to float4s
+constexpr int kStepBlock = 4;                                 // time steps per loop trip (BSM, FSM)
+constexpr int kInFloats = kChunk + kMaxK1D + 2 * kStepBlock;  // chunk + k - 1 inputs, plus the look-ahead of BSM's reads
 constexpr int kFfsWidth = 16;                                 // PEs of an FFS array
+constexpr int kFfsPasses = kChunk / kWave;                    // 64 outputs (four arrays) per pass
 
 enum ArrayDesign { kBsm, kFsm, kFfs };
 
@@ -54,6 +56,46 @@ __device__ __forceinline__ void stage_out(float* __restrict__ y, long long base,
         store4_guarded(y, base + i, m, v);
     }
 }
+
+__device__ __forceinline__ int clamp_index(int i, int hi) { return i < 0 ? 0 : (i > hi ? hi : i); }
+
+// One PE of an FSM array and kStepBlock of its time steps.  PE q works on output c = t + q
+// at step t and needs x(c + q) = x(t + 2q).  EDGE trips clamp that index into the array's
+// window (the PEs it is clamped for are filling or draining), let a PE load its own input
+// for its first output, and store only steps 0 <= t < seg.
+struct FsmArray {
+    bool top, bottom;
+    int q, seg, hi;
+    float wq;
+    float z = 0.0f, x1 = 0.0f, x2 = 0.0f;                                  // X of one and of two steps ago
+
+    template <bool EDGE>
+    __device__ __forceinline__ void steps(int t0, const float* seg_in, float* seg_out)
+    {
+        float xl[kStepBlock], zs[kStepBlock];
+#pragma unroll
+        for (int j = 0; j < kStepBlock; ++j) {
+            const int idx = t0 + j + 2 * q;
+            xl[j] = seg_in[EDGE ? clamp_index(idx, hi) : idx];
+        }
+#pragma unroll
+        for (int j = 0; j < kStepBlock; ++j) {
+            const int t = t0 + j;
+            const float xup = from_lane_above(x2);                         // X(c,q) <- X(c-1,q+1), two steps old
+            const float xt = (top || (EDGE && t + q == 0)) ? xl[j] : xup;
+            const float zup = from_lane_above(z);                          // Z(c,q) <- Z(c,q+1) from PE q+1
+            z = __builtin_fmaf(xt, wq, top ? 0.0f : zup);
+            x2 = x1;
+            x1 = xt;
+            zs[j] = z;
+        }
+        if (bottom) {                                                      // output c = t leaves PE 0
+#pragma unroll
+            for (int j = 0; j < kStepBlock; ++j)
+                if (!EDGE || (t0 + j >= 0 && t0 + j < seg)) seg_out[t0 + j] = zs[j];
+        }
+    }
+};
 
 // The taps are the first kernel argument (offset 0 of the kernel-argument segment).
 template <int DESIGN>
@@ -88,54 +130,83 @@ __global__ __launch_bounds__(kBlock) void conv1d_array_kernel(Taps1D taps, const
             float z = 0.0f;
             if (DESIGN == kBsm) {
                 const bool first = q == 0, last = active && q == k - 1;
-                for (int t = 0; t < seg + k - 1; ++t) {
-                    const float xin = seg_in[t];                           // broadcast to the array's K PEs
-                    // Z(c,q) <- Z(c,q-1) from PE q-1.  The lane move runs in ALL lanes and the
-                    // select comes after it: a DPP read from a lane that is masked off returns 0.
-                    const float zdown = from_lane_below(z);
-                    const float zprev = first ? 0.0f : zdown;
-                    z = __builtin_fmaf(xin, wq, zprev);
-                    if (last && t >= k - 1) seg_out[t - (k - 1)] = z;     // output c = t-(K-1) leaves PE K-1
+                // Four time steps per trip: their inputs are one aligned 16-byte LDS read, issued
+                // one trip ahead.  Steps past the segment's end (t >= seg + k - 1) read staged or
+                // stale LDS words inside this wavefront's buffer and store nothing.
+                f4 xv = *reinterpret_cast<const f4*>(seg_in);
+                for (int t0 = 0; t0 < seg + k - 1; t0 += kStepBlock) {
+                    const f4 xnext = *reinterpret_cast<const f4*>(seg_in + t0 + kStepBlock);
+                    const float xin[kStepBlock] = {xv.x, xv.y, xv.z, xv.w};   // x(t) goes to the array's K PEs
+                    float zs[kStepBlock];
+#pragma unroll
+                    for (int j = 0; j < kStepBlock; ++j) {
+                        // Z(c,q) <- Z(c,q-1) from PE q-1.  The lane move runs in ALL lanes and the
+                        // select comes after it: a DPP read from a lane that is masked off returns 0.
+                        const float zdown = from_lane_below(z);
+                        z = __builtin_fmaf(xin[j], wq, first ? 0.0f : zdown);
+                        zs[j] = z;
+                    }
+                    // Output c leaves PE K-1 at t = c + K - 1.
+                    const int c0 = t0 - (k - 1);
+                    if (c0 >= 0 && c0 + kStepBlock <= seg) {               // the usual trip: all four are outputs
+                        if (last) {
+#pragma unroll
+                            for (int j = 0; j < kStepBlock; ++j) seg_out[c0 + j] = zs[j];
+                        }
+                    } else if (last) {
+#pragma unroll
+                        for (int j = 0; j < kStepBlock; ++j)
+                            if (c0 + j >= 0 && c0 + j < seg) seg_out[c0 + j] = zs[j];
+                    }
+                    xv = xnext;
                 }
             } else {
-                const bool top = q == k - 1, bottom = active && q == 0;
-                float x1 = 0.0f, x2 = 0.0f;                                // X of one and of two steps ago
-                for (int t = -(k - 1); t < seg; ++t) {
-                    int idx = t + 2 * q;                                   // = c + q for c = t + q
-                    idx = idx < 0 ? 0 : (idx > seg + k - 2 ? seg + k - 2 : idx);
-                    const float xload = seg_in[idx];
-                    const float xup = from_lane_above(x2);                 // X(c,q) <- X(c-1,q+1), two steps old
-                    const float xt = (top || t + q == 0) ? xload : xup;
-                    const float zup = from_lane_above(z);                  // Z(c,q) <- Z(c,q+1) from PE q+1
-                    const float zprev = top ? 0.0f : zup;
-                    z = __builtin_fmaf(xt, wq, zprev);
-                    x2 = x1;
-                    x1 = xt;
-                    if (bottom && t >= 0) seg_out[t] = z;                  // output c = t leaves PE 0
+                FsmArray pe;
+                pe.top = q == k - 1;
+                pe.bottom = active && q == 0;
+                pe.q = q;
+                pe.wq = wq;
+                pe.seg = seg;
+                pe.hi = seg + k - 2;
+                // Trips whose steps all lie in 1 <= t, t + 2(K-1) <= hi, t < seg need no index
+                // clamp, no test for a PE's first output and no test before a store.
+                const int t_plain_end = (seg < pe.hi - 2 * (k - 1) + 1 ? seg : pe.hi - 2 * (k - 1) + 1) - kStepBlock;
+                for (int t0 = -(k - 1); t0 < seg; t0 += kStepBlock) {
+                    if (t0 >= 1 && t0 <= t_plain_end) pe.template steps<false>(t0, seg_in, seg_out);
+                    else                              pe.template steps<true>(t0, seg_in, seg_out);
                 }
             }
         } else {
+            // All chunk / 64 passes of the wavefront advance together, one time step at a time:
+            // the weights' journey through the PEs is the same in every pass, so it is made once,
+            // and the passes' independent X and Z chains overlap each other's LDS latency.
             const int c = lane & (kFfsWidth - 1);
             const int a0 = lane - c;                                       // first output of this lane's array in a pass
             const bool first = c == 0;
-            for (int pass = 0; pass < chunk / kWave; ++pass) {
-                const float* arr_in = in + pass * kWave + a0;
-                float z = 0.0f, xt = 0.0f, w1 = 0.0f, w2 = 0.0f;
-                for (int t = 0; t < 2 * (kFfsWidth - 1) + k; ++t) {
-                    const int q = t - 2 * c;
-                    int idx = t - c;                                       // = c + q
-                    idx = idx < 0 ? 0 : (idx > kFfsWidth + k - 2 ? kFfsWidth + k - 2 : idx);
-                    const float xload = arr_in[idx];
-                    const float xdown = from_lane_below(xt);               // X(c,q) <- X(c-1,q+1), one step old
-                    xt = (first || q == k - 1) ? xload : xdown;
-                    const float wdown = from_lane_below(w2);               // W(c,q) <- W(c-1,q), two steps old
-                    const float wt = first ? tw[t < k ? t : k] : wdown;     // w(q) for q = t < K, else the zero behind the taps
-                    if (q >= 0 && q < k) z = __builtin_fmaf(xt, wt, z);
-                    w2 = w1;
-                    w1 = wt;
+            const int hi = kFfsWidth + k - 2;
+            float z[kFfsPasses], xt[kFfsPasses];
+#pragma unroll
+            for (int p = 0; p < kFfsPasses; ++p) z[p] = xt[p] = 0.0f;
+            float w1 = 0.0f, w2 = 0.0f;
+            for (int t = 0; t < 2 * (kFfsWidth - 1) + k; ++t) {
+                const int q = t - 2 * c;
+                const float* arr_in = in + a0 + clamp_index(t - c, hi);    // x(c + q), c + q = t - c
+                const float wdown = from_lane_below(w2);                   // W(c,q) <- W(c-1,q), two steps old
+                const float wt = first ? tw[t < k ? t : k] : wdown;        // w(q) for q = t < K, else the zero behind the taps
+                const bool fresh = first || q == k - 1;                    // this PE is the first to use x(c + q)
+                const bool busy = q >= 0 && q < k;
+#pragma unroll
+                for (int p = 0; p < kFfsPasses; ++p) {
+                    const float xload = arr_in[p * kWave];
+                    const float xdown = from_lane_below(xt[p]);            // X(c,q) <- X(c-1,q+1), one step old
+                    xt[p] = fresh ? xload : xdown;
+                    z[p] = busy ? __builtin_fmaf(xt[p], wt, z[p]) : z[p];
                 }
-                out[pass * kWave + lane] = z;
+                w2 = w1;
+                w1 = wt;
             }
+#pragma unroll
+            for (int p = 0; p < kFfsPasses; ++p) out[p * kWave + lane] = z[p];
         }
     }
     __syncthreads();
@@ -151,7 +222,10 @@ hipError_t launch_array(const float* x, size_t n, const float* w, int k, float* 
     int seg = 0, chunk = kChunk;
     if (DESIGN != kFfs) {
         const int arrays = kWave / k;
-        seg = (kChunk / arrays) & ~3;                                      // segments start on float4 boundaries
+        // Segments start on float4 boundaries, and their length is 4 (mod 8) floats, so that
+        // the arrays of a wavefront, which read in + a * seg + t at the same step, start in
+        // different LDS banks instead of all in one.
+        seg = (((kChunk / arrays) - 4) & ~7) + 4;
         chunk = arrays * seg;
     }
     const long long waves = (m + chunk - 1) / chunk;

@@ -119,7 +119,7 @@ def wave64(design: str, n_taps: int, groups: int = 4, tile: int = 4, lanes: int 
         outs, steps = n_pe, n_taps + tile - 1
     elif design in ("BSM", "FSM"):
         arrays = lanes // n_taps
-        seg = (1024 // arrays) & ~3
+        seg = (((1024 // arrays) - 4) & ~7) + 4
         n_pe, outs, steps = lanes, arrays * seg, seg + n_taps - 1
     elif design == "FFS":
         width = 16
