@@ -11,7 +11,9 @@ Pins (see ``tests/test_oracle_pins.py`` and ``tests/test_ure_recurrences.py``):
 hand-expanded sums, delta filters, linearity, separability, constant / ramp /
 box closed forms, integer-exact data, numpy's and torch's float64 routines as a
 library special case, the paper's recurrence equations (Section 3.1, Table 2,
-Section 5) evaluated literally, and the printed values of Table 4.
+Section 5) evaluated literally, and the printed values of Table 4; the strided
+form also against hand sums, every stride-th output of the stride-1 form, numpy's
+correlate subsampled, and the stride-2 recurrences of Table 2.
 Nothing here is "parity unpinned".
 """
 from __future__ import annotations
@@ -48,6 +50,10 @@ def _load():
         for name in ("oracle_conv1d", "oracle_absdot1d"):
             fn = getattr(lib, name)
             fn.argtypes = [fp, ctypes.c_size_t, fp, ctypes.c_int, dp, ctypes.c_int]
+            fn.restype = ctypes.c_int
+        for name in ("oracle_conv1d_strided", "oracle_absdot1d_strided"):
+            fn = getattr(lib, name)
+            fn.argtypes = [fp, ctypes.c_size_t, fp, ctypes.c_int, ctypes.c_int, dp, ctypes.c_int]
             fn.restype = ctypes.c_int
         for name in ("oracle_conv2d", "oracle_absdot2d"):
             fn = getattr(lib, name)
@@ -93,6 +99,19 @@ def _run1d(fname, x, w, nthreads):
     return y
 
 
+def _run1d_strided(fname, x, w, stride, nthreads):
+    x = _f32(x, 1)
+    w = _f32(w, 1)
+    n, k = x.shape[0], w.shape[0]
+    if k < 1 or k > n or stride < 1:
+        raise ValueError("need 1 <= k <= n and stride >= 1")
+    y = np.empty((n - k) // stride + 1, dtype=np.float64)
+    rc = getattr(_load(), fname)(_fptr(x), n, _fptr(w), k, int(stride), _dptr(y), int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"{fname} failed with status {rc}")
+    return y
+
+
 def _run2d(fname, x, f, nthreads):
     x = _f32(x, 2)
     f = _f32(f, 2)
@@ -111,6 +130,15 @@ def _run2d(fname, x, f, nthreads):
 def conv1d(x, w, nthreads: int = 1) -> np.ndarray:
     """Eq. 2: y[c] = sum_q x[c+q] * w[q]; fp32 inputs, fp64 result, length n-k+1."""
     return _run1d("oracle_conv1d", x, w, nthreads)
+
+
+def conv1d_strided(x, w, stride: int, nthreads: int = 1) -> np.ndarray:
+    """Table 2, row 3 right, read as y[c] = sum_q x[stride*c+q] * w[q]; length (n-k)//stride + 1."""
+    return _run1d_strided("oracle_conv1d_strided", x, w, stride, nthreads)
+
+
+def absdot1d_strided(x, w, stride: int, nthreads: int = 1) -> np.ndarray:
+    return _run1d_strided("oracle_absdot1d_strided", x, w, stride, nthreads)
 
 
 def conv2d(x, f, nthreads: int = 1) -> np.ndarray:

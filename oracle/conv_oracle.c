@@ -7,10 +7,17 @@
  *   1-D (paper Eq. 2, Section 3.1):   Z(c)   = sum_q          x(c+q)     * w(q)
  *   2-D (paper Eq. 3, Section 5):     Z(c,r) = sum_q sum_p    x(c+q,r+p) * w(q,p)
  *
+ * and the strided 1-D form that the stride-2 FBS design of Table 2 (row 3 right)
+ * computes:                            Z(c)   = sum_q          x(S*c+q)   * w(q)
+ *
  * Readings taken where the paper is silent:
  *   - no filter flip (the equations index x(c+q), so this is cross-correlation);
  *   - "valid" extent: the recurrences load x(c+q) for c = C-1, q = Q-1, so the
  *     input has C+Q-1 elements and there is no padding;
+ *   - stride S: the table prints x(c+q) for the stride-2 design too, but its
+ *     dependence X(c,q) = X(c+1,q-2) only holds for x(2c+q) (x(2(c+1)+q-2) is the
+ *     same element), so that is the definition taken; outputs exist for every c
+ *     with S*c + k - 1 < n, i.e. floor((n-k)/S) + 1 of them;
  *   - the paper's fast (systolic) axis c,q is the column of a row-major image
  *     and r,p is the row:  y[r][c] = sum_p sum_q f[p][q] * x[r+p][c+q].
  *
@@ -73,6 +80,29 @@ int oracle_conv1d(const float *x, size_t n, const float *w, int k,
 }
 
 /*
+ * Strided Eq. 2 (Table 2, row 3 right, read with x(S*c+q)).
+ * x: n floats, w: k floats, y: (n-k)/stride + 1 doubles.  stride 1 is Eq. 2.
+ */
+int oracle_conv1d_strided(const float *x, size_t n, const float *w, int k, int stride,
+                          double *y, int nthreads)
+{
+    if (!x || !w || !y || k < 1 || (size_t)k > n || stride < 1) return ORACLE_BAD_ARG;
+    const long long m = (long long)((n - (size_t)k) / (size_t)stride + 1);
+    const int nt = clamp_threads(nthreads);
+    (void)nt;
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(nt) schedule(static)
+#endif
+    for (long long c = 0; c < m; ++c) {
+        double z = 0.0;
+        for (int q = 0; q < k; ++q)
+            z += (double)x[(long long)stride * c + q] * (double)w[q];
+        y[c] = z;
+    }
+    return ORACLE_OK;
+}
+
+/*
  * Eq. 3.  x: h rows of w_img floats, row stride x_pitch elements.
  * f: kh*kw floats, row-major.  y: (h-kh+1) rows of (w_img-kw+1) doubles,
  * row stride y_pitch elements.
@@ -123,6 +153,27 @@ int oracle_absdot1d(const float *x, size_t n, const float *w, int k,
         double z = 0.0;
         for (int q = 0; q < k; ++q) {
             double xv = (double)x[c + q], wv = (double)w[q];
+            z += (xv < 0 ? -xv : xv) * (wv < 0 ? -wv : wv);
+        }
+        s[c] = z;
+    }
+    return ORACLE_OK;
+}
+
+int oracle_absdot1d_strided(const float *x, size_t n, const float *w, int k, int stride,
+                            double *s, int nthreads)
+{
+    if (!x || !w || !s || k < 1 || (size_t)k > n || stride < 1) return ORACLE_BAD_ARG;
+    const long long m = (long long)((n - (size_t)k) / (size_t)stride + 1);
+    const int nt = clamp_threads(nthreads);
+    (void)nt;
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(nt) schedule(static)
+#endif
+    for (long long c = 0; c < m; ++c) {
+        double z = 0.0;
+        for (int q = 0; q < k; ++q) {
+            double xv = (double)x[(long long)stride * c + q], wv = (double)w[q];
             z += (xv < 0 ? -xv : xv) * (wv < 0 ? -wv : wv);
         }
         s[c] = z;

@@ -263,3 +263,50 @@ def test_pins_would_catch_a_flipped_or_transposed_filter():
     img = np.arange(1, 10, dtype=np.float32).reshape(3, 3)
     f = np.array([[1, 2], [3, 4]], np.float32)
     assert not np.array_equal(oracle.conv2d(img, f.T.copy()), np.array([[37.0, 47.0], [67.0, 77.0]]))
+
+
+# --------------------------------------------------------------- strided 1-D (Table 2, row 3 right)
+def test_strided_hand_sums():
+    # y[c] = sum_q x[2c+q] w[q], written out by hand for n = 8, k = 3: c = 0, 1, 2 (2*2+2 = 6 < 8; c = 3 needs x[8]).
+    x = np.array([1, -2, 3, 5, -7, 11, 13, -17], np.float32)
+    w = np.array([2, -1, 4], np.float32)
+    want = np.array([1 * 2 + 2 * 1 + 3 * 4, 3 * 2 - 5 * 1 - 7 * 4, -7 * 2 - 11 * 1 + 13 * 4], np.float64)
+    assert np.array_equal(oracle.conv1d_strided(x, w, 2), want)
+    # stride 3, k = 2: c = 0, 1, 2 (windows start at 0, 3, 6)
+    w2 = np.array([3, 5], np.float32)
+    want3 = np.array([1 * 3 - 2 * 5, 5 * 3 - 7 * 5, 13 * 3 - 17 * 5], np.float64)
+    assert np.array_equal(oracle.conv1d_strided(x, w2, 3), want3)
+
+
+@pytest.mark.parametrize("n,k,stride", [(41, 5, 2), (40, 5, 2), (64, 2, 2), (65, 16, 2), (33, 1, 2), (50, 7, 3), (9, 9, 2), (10, 9, 2), (11, 9, 2)])
+def test_strided_is_every_stride_th_output_and_length(n, k, stride):
+    rng = np.random.default_rng(n * 100 + k)
+    x = rng.uniform(-1, 1, n).astype(np.float32)
+    w = rng.uniform(-1, 1, k).astype(np.float32)
+    y = oracle.conv1d_strided(x, w, stride)
+    assert y.shape == ((n - k) // stride + 1,)
+    assert np.array_equal(y, oracle.conv1d(x, w)[::stride])          # same fp64 sums in the same order
+    lib = np.correlate(x.astype(np.float64), w.astype(np.float64), mode="valid")[::stride]
+    assert np.allclose(y, lib, rtol=0, atol=1e-13)
+    s = oracle.absdot1d_strided(x, w, stride)
+    assert np.array_equal(s, oracle.absdot1d(x, w)[::stride])
+
+
+def test_strided_stride_one_is_eq2_and_delta_picks_x_2c_plus_j():
+    rng = np.random.default_rng(3)
+    x = rng.uniform(-1, 1, 100).astype(np.float32)
+    w = rng.uniform(-1, 1, 6).astype(np.float32)
+    assert np.array_equal(oracle.conv1d_strided(x, w, 1), oracle.conv1d(x, w))
+    for j in range(6):
+        d = np.zeros(6, np.float32)
+        d[j] = 1
+        got = oracle.conv1d_strided(x, d, 2)
+        assert np.array_equal(got, x[j:j + 2 * len(got):2].astype(np.float64))   # a swapped "2c" / "q" would fail here
+
+
+def test_strided_bad_arguments():
+    x = np.zeros(8, np.float32)
+    with pytest.raises(ValueError):
+        oracle.conv1d_strided(x, np.zeros(3, np.float32), 0)
+    with pytest.raises(ValueError):
+        oracle.conv1d_strided(x, np.zeros(9, np.float32), 2)

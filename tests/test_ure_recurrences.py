@@ -45,6 +45,9 @@ def test_stride2_fbs_recurrence_reading():
     x, w = _ints(77, 41, 5)
     full = oracle.conv1d(x, w)
     assert np.array_equal(ure_1d("FBS", x, w, stride=2), full[::2])
+    for n, k in [(41, 5), (40, 5), (30, 2), (37, 16), (19, 1)]:
+        x, w = _ints(n * 10 + k, n, k)
+        assert np.array_equal(ure_1d("FBS", x, w, stride=2), oracle.conv1d_strided(x, w, 2))
 
 
 @pytest.mark.parametrize("shape,kshape", [((6, 9), (2, 2)), ((8, 12), (5, 5)), ((5, 7), (3, 1)), ((4, 11), (1, 4)), ((9, 9), (3, 5))])
