@@ -2,6 +2,8 @@
 """Benchmark of libsysconv on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extras] [--no-cpu]
+    python bench.py --design-space      # the six 1-D designs of Table 2 at n = 2^26, k = 2, 5, 16
+    python bench.py --paper-shape       # the grid of the paper's Section 6 experiment (671 M outputs per case)
 
 A step is one pass of the hot path -- weight residency, input load, systolic time
 loop, output store -- over the large 1-D workload (n = 2^26 fp32 inputs, 16
@@ -53,6 +55,10 @@ def _parse():
     ap.add_argument("--design-space", action="store_true",
                     help="only time the six 1-D designs of the paper's Table 2 at n=2^26 for k in {2, 5, 16} "
                          "(the paper's Table 3 uses k = 2 and 5) and print that table as JSON")
+    ap.add_argument("--paper-shape", action="store_true",
+                    help="only time the grid of the paper's Section 6 experiment: 10 Mi 'threads' of 16x4 outputs each "
+                         "(671 M outputs), 1-D k in {2, 5} at stride 1 (six designs) and stride 2 (FBS), 2-D 2x2 and "
+                         "5x5 (SBM, FBS, BFS); throughput = outputs / time, as in the paper; prints JSON")
     return ap.parse_args()
 
 
@@ -156,6 +162,68 @@ def main() -> int:
         print(json.dumps({"design_space_1d": rows, "n": wl.x_shape[0], "data": "synthetic",
                           "note": "paper column: Table 3 (Intel GEN9.5, relative to its hardware sampler), "
                                   "rescaled to FBS = 1; context, not a target"}))
+        return 0
+
+    if args.paper_shape:
+        threads, per_thread = 10 * (1 << 20), 16 * 4        # Section 6: "over 10 millions of threads", 16*4 outputs each
+        outputs = threads * per_thread
+        paper_1d = {"SBM": (157, 147), "BSM": (67, 49), "FSM": (56, 39), "BFS": (56, 48), "FFS": (33, 30),
+                    "FBS": (159, 157)}                      # Table 3, % of the hardware sampler (k = 2, 5)
+        paper_2d = {"SBM": (92, 20), "FBS": (114, 24)}      # Table 5 (2x2, 5x5)
+        rng = np.random.default_rng(158846)
+        rows = []
+
+        def timed(launch, read_floats, taps_per_out, row):
+            _, k_mean, _ = time_launches(launch, 5, 1)
+            row.update({"kernel_us": round(k_mean * 1e6, 1), "Goutputs/s": round(outputs / k_mean / 1e9, 2),
+                        "GB/s": round(4 * (read_floats + outputs) / k_mean / 1e9, 1),
+                        "Gtap/s": round(outputs * taps_per_out / k_mean / 1e9, 1)})
+            rows.append(row)
+            print(json.dumps(row), file=sys.stderr, flush=True)
+
+        def rotate(make_x, y_shape):
+            dxs = [make_x() for _ in range(2)]              # 2 x (>= 5 GB) per pass: far past the memory-side cache
+            dys = [torch.empty(y_shape, dtype=torch.float32, device="cuda") for _ in range(2)]
+            return dxs, dys, {"i": 0}
+
+        x1 = torch.from_numpy(W.uniform_f32(rng, -1.0, 1.0, (2 * outputs + 8,)))      # longest 1-D input (stride 2)
+        for stride in (1, 2):
+            for ki, k in enumerate((2, 5)):
+                taps = W.uniform_f32(np.random.default_rng(15884 + k), -1.0, 1.0, (k,))
+                n = stride * (outputs - 1) + k
+                dxs, dys, st = rotate(lambda: x1[:n].cuda(), (outputs,))
+                for proj in (("FBS", "SBM", "BFS", "BSM", "FSM", "FFS") if stride == 1 else ("FBS",)):
+                    def launch():
+                        i = st["i"] = (st["i"] + 1) % 2
+                        B.sys_conv1d_strided(dxs[i], taps, stride, dys[i], projection=proj)
+                    row = {"conv": "1-D", "k": k, "stride": stride, "design": proj}
+                    if stride == 1:
+                        row["paper_relative_to_FBS"] = round(paper_1d[proj][ki] / paper_1d["FBS"][ki], 3)
+                    timed(launch, n, k, row)
+                del dxs, dys
+        del x1
+        oh, ow = 16384, outputs // 16384
+        x2 = torch.from_numpy(W.uniform_f32(rng, -1.0, 1.0, (oh + 4, ow + 4)))
+        for ki, kk in enumerate((2, 5)):
+            f = W.uniform_f32(np.random.default_rng(15884 + 10 * kk), -1.0, 1.0, (kk, kk))
+            h, w_img = oh + kk - 1, ow + kk - 1
+            dxs, dys, st = rotate(lambda: x2[:h, :w_img].contiguous().cuda(), (oh, ow))
+            for proj in ("FBS", "SBM", "BFS"):
+                def launch():
+                    i = st["i"] = (st["i"] + 1) % 2
+                    B.sys_conv2d(dxs[i], f, dys[i], projection=proj)
+                row = {"conv": "2-D", "k": f"{kk}x{kk}", "stride": 1, "design": proj}
+                if proj in paper_2d:
+                    row["paper_relative_to_FBS"] = round(paper_2d[proj][ki] / paper_2d["FBS"][ki], 3)
+                timed(launch, h * w_img, kk * kk, row)
+            del dxs, dys
+        ref = {(r["conv"], r["k"], r["stride"]): r["kernel_us"] for r in rows if r["design"] == "FBS"}
+        for r in rows:
+            r["relative_to_FBS"] = round(ref[(r["conv"], r["k"], r["stride"])] / r["kernel_us"], 3)
+        print(json.dumps({"paper_shape": rows, "threads": threads, "outputs_per_thread": per_thread,
+                          "outputs": outputs, "data": "synthetic",
+                          "note": "paper columns: Tables 3 and 5 (Intel GEN9.5, relative to its hardware sampler), "
+                                  "rescaled to FBS = 1; context, not a target; the paper prints no stride-2 figures"}))
         return 0
 
     # ------------------------------------------------------------ headline step

@@ -103,6 +103,25 @@ int sys_conv1d(const float *d_x, size_t n,
                int projection, hipStream_t stream);
 
 /*
+ * Strided 1-D valid convolution:  d_y[c] = sum_{q<k} d_x[stride*c+q] * h_w[q],
+ * c < (n-k)/stride + 1  (integer division).  This is what the stride-2 FBS design of
+ * Table 2 (row 3 right) computes: its hand-over X(c,q) = X(c+1,q-2) is the identity
+ * x(2c+q) = x(2(c+1)+q-2); the cell's printed "x(c+q)" is read as x(2c+q).
+ *   stride 1  identical to sys_conv1d (every projection).
+ *   stride 2  FBS only (SYS_PROJ_AUTO or SYS_PROJ_FBS); any 1 <= k <= min(n, SYS_MAX_K1D).
+ *   other strides, or other projections at stride 2: SYS_ERR_UNSUPPORTED
+ *             (sys_conv1d_strided_has reports it); stride < 1: SYS_ERR_SIZE.
+ *   d_x   device, n floats (read only);  d_y  device, (n-k)/stride + 1 floats (written).
+ */
+int sys_conv1d_strided(const float *d_x, size_t n,
+                       const float *h_w, int k, int stride,
+                       float *d_y,
+                       int projection, hipStream_t stream);
+
+/* 1 if sys_conv1d_strided(projection) is built for a k-tap filter at this stride, else 0. */
+int sys_conv1d_strided_has(int projection, int k, int stride);
+
+/*
  * 2-D valid convolution, Eq. 3, single channel, row-major:
  *   d_y[r*y_pitch + c] = sum_{p<kh} sum_{q<kw} d_x[(r+p)*x_pitch + c+q] * h_f[p*kw+q]
  * for r < h-kh+1, c < w-kw+1.

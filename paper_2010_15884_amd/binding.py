@@ -23,7 +23,8 @@ PROJECTIONS = {"AUTO": SYS_PROJ_AUTO, "FBS": SYS_PROJ_FBS, "BFS": SYS_PROJ_BFS, 
 SYS_MAX_K1D = 64
 SYS_MAX_K2D = 15
 
-EXPORTS = ["sys_conv1d", "sys_conv2d", "sys_conv1d_has", "sys_conv2d_has", "sys_copy_f32", "sys_status_string",
+EXPORTS = ["sys_conv1d", "sys_conv1d_strided", "sys_conv2d", "sys_conv1d_has", "sys_conv1d_strided_has",
+           "sys_conv2d_has", "sys_copy_f32", "sys_status_string",
            "sys_projection_name", "sys_last_hip_error", "sys_version"]
 
 _lib = None
@@ -54,6 +55,10 @@ def lib() -> ctypes.CDLL:
         L.sys_conv1d.restype = ci
         L.sys_conv2d.argtypes = [vp, ci, ci, sz, fp, ci, ci, vp, sz, ci, vp]
         L.sys_conv2d.restype = ci
+        L.sys_conv1d_strided.argtypes = [vp, sz, fp, ci, ci, vp, ci, vp]
+        L.sys_conv1d_strided.restype = ci
+        L.sys_conv1d_strided_has.argtypes = [ci, ci, ci]
+        L.sys_conv1d_strided_has.restype = ci
         L.sys_conv1d_has.argtypes = [ci, ci]
         L.sys_conv1d_has.restype = ci
         L.sys_conv2d_has.argtypes = [ci, ci, ci]
@@ -112,6 +117,13 @@ def _device_f32(t, what):
     return t
 
 
+def _room_1d(d_y, m):
+    """The library writes m floats through the pointer it is given: make sure the tensor has them."""
+    _device_f32(d_y, "d_y")
+    if d_y.dim() != 1 or not d_y.is_contiguous() or d_y.numel() < m:
+        raise ValueError(f"d_y must be a contiguous 1-D tensor with room for {m} outputs")
+
+
 def sys_conv1d(d_x, h_w, d_y=None, projection="AUTO", stream=None):
     """y[c] = sum_q x[c+q] w[q].  d_x: 1-D float32 CUDA tensor; h_w: host taps.
     Returns d_y (allocated with torch if not given)."""
@@ -123,9 +135,26 @@ def sys_conv1d(d_x, h_w, d_y=None, projection="AUTO", stream=None):
     n, k = d_x.shape[0], w.shape[0]
     if d_y is None:
         d_y = torch.empty(max(n - k + 1, 0), dtype=torch.float32, device=d_x.device)
-    _device_f32(d_y, "d_y")
+    _room_1d(d_y, max(n - k + 1, 0))
     _check(lib().sys_conv1d(d_x.data_ptr(), n, w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), k,
                             d_y.data_ptr(), _proj(projection), _stream_handle(stream)))
+    return d_y
+
+
+def sys_conv1d_strided(d_x, h_w, stride, d_y=None, projection="AUTO", stream=None):
+    """y[c] = sum_q x[stride*c+q] w[q], (n-k)//stride + 1 outputs.  Arguments as sys_conv1d."""
+    import torch
+    _device_f32(d_x, "d_x")
+    if d_x.dim() != 1 or not d_x.is_contiguous():
+        raise ValueError("d_x must be a contiguous 1-D tensor")
+    w = _taps(h_w)
+    n, k, stride = d_x.shape[0], w.shape[0], int(stride)
+    m = (n - k) // stride + 1 if (stride >= 1 and n >= k) else 0
+    if d_y is None:
+        d_y = torch.empty(m, dtype=torch.float32, device=d_x.device)
+    _room_1d(d_y, m)
+    _check(lib().sys_conv1d_strided(d_x.data_ptr(), n, w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), k, stride,
+                                    d_y.data_ptr(), _proj(projection), _stream_handle(stream)))
     return d_y
 
 
@@ -146,6 +175,8 @@ def sys_conv2d(d_x, h_f, d_y=None, projection="AUTO", stream=None):
     _device_f32(d_y, "d_y")
     if d_y.dim() != 2 or d_y.stride(1) != 1:
         raise ValueError("d_y must be 2-D with unit column stride")
+    if d_y.shape[0] < max(h - kh + 1, 0) or d_y.shape[1] < max(w - kw + 1, 0):
+        raise ValueError(f"d_y must have room for {h - kh + 1} x {w - kw + 1} outputs")
     _check(lib().sys_conv2d(d_x.data_ptr(), h, w, d_x.stride(0),
                             f.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), kh, kw,
                             d_y.data_ptr(), d_y.stride(0), _proj(projection), _stream_handle(stream)))
@@ -154,6 +185,10 @@ def sys_conv2d(d_x, h_f, d_y=None, projection="AUTO", stream=None):
 
 def sys_conv1d_has(projection, k: int) -> bool:
     return bool(lib().sys_conv1d_has(_proj(projection), int(k)))
+
+
+def sys_conv1d_strided_has(projection, k: int, stride: int) -> bool:
+    return bool(lib().sys_conv1d_strided_has(_proj(projection), int(k), int(stride)))
 
 
 def sys_conv2d_has(projection, kh: int, kw: int) -> bool:

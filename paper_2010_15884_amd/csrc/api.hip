@@ -64,6 +64,28 @@ int sys_conv1d(const float* d_x, size_t n, const float* h_w, int k, float* d_y, 
     }
 }
 
+int sys_conv1d_strided(const float* d_x, size_t n, const float* h_w, int k, int stride, float* d_y, int projection,
+                       hipStream_t stream)
+{
+    if (stride == 1) return sys_conv1d(d_x, n, h_w, k, d_y, projection, stream);
+    if (!d_x || !h_w || !d_y) return SYS_ERR_NULL;
+    if (k < 1 || (size_t)k > n || stride < 1) return SYS_ERR_SIZE;
+    if (!known_projection(projection) || k > SYS_MAX_K1D) return SYS_ERR_UNSUPPORTED;
+    if (!sys_conv1d_strided_has(projection, k, stride)) return SYS_ERR_UNSUPPORTED;
+    if (misaligned(d_x) || misaligned(d_y)) return SYS_ERR_UNSUPPORTED;
+    if (n > ((size_t)1 << 40)) return SYS_ERR_UNSUPPORTED;
+    const size_t m = (n - (size_t)k) / (size_t)stride + 1;
+    if (ranges_overlap(d_x, n * sizeof(float), d_y, m * sizeof(float))) return SYS_ERR_ALIAS;
+    return hip_status(sysconv::launch_conv1d_fbs_stride2(d_x, n, h_w, k, d_y, stream));
+}
+
+int sys_conv1d_strided_has(int projection, int k, int stride)
+{
+    if (stride == 1) return sys_conv1d_has(projection, k);
+    if (k < 1 || k > SYS_MAX_K1D || stride != 2) return 0;
+    return (projection == SYS_PROJ_AUTO || projection == SYS_PROJ_FBS) ? 1 : 0;
+}
+
 int sys_conv1d_has(int projection, int k)
 {
     if (k < 1 || k > SYS_MAX_K1D) return 0;

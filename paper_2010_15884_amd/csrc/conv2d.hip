@@ -20,6 +20,59 @@ __device__ __forceinline__ int xcd_contiguous(int b, int per_xcd)
     return (b % kXcds) * per_xcd + (b / kXcds);
 }
 
+// Wavefront -> (row block, strip) for the kernels whose wavefronts each take one
+// block of rows of one 256-column strip.
+//   - The four wavefronts of a workgroup take four vertically adjacent row blocks of
+//     one strip: the halo rows they share are fetched by one CU at about the same time.
+//   - Workgroups are ordered strip after strip across a band of `side` strips, then one
+//     step down, and on to the next band when the bottom is reached.  side = 1 walks
+//     down single strips, which puts the pitch between all concurrent requests;
+//     side = 16 keeps long contiguous pieces of image rows in flight (band_width()).
+//   - Every XCD owns one contiguous run of workgroups in that order, so row blocks that
+//     share halo rows meet in one L2.
+// Returns false for a wavefront without work (uniform per wavefront).
+__device__ __forceinline__ void band_order(int g, int steps_down, int strips, int side, int& down, int& strip)
+{
+    const int per_band = side * steps_down;
+    const int full = strips / side;                                        // bands of `side` strips
+    const int band = min(g / per_band, full);
+    const int width = band < full ? side : strips - full * side;           // the last band takes what is left (> 0 here)
+    const int within = g - band * per_band;
+    down = within / width;
+    strip = band * side + (within - down * width);
+}
+
+__device__ __forceinline__ bool wave_tile(int per_xcd, int row_blocks, int strips, int side, int& rb, int& strip)
+{
+    constexpr int kWaves = kBlock / kWave;
+    const int g = xcd_contiguous(blockIdx.x, per_xcd);
+    const int rb_groups = (row_blocks + kWaves - 1) / kWaves;
+    if (g >= rb_groups * strips) return false;
+    int rbg;
+    band_order(g, rb_groups, strips, side, rbg, strip);
+    rb = rbg * kWaves + wave_in_block();
+    return rb < row_blocks;
+}
+
+// Strips per band, from in-process A/B runs on MI355X (block-form BFS, 5x5 unless noted;
+// us with 1 / 16 strips per band):
+//   pitch 16 KB (4096^2) 28.6 / 33.2, 20 KB 46 / 48, 24 KB and 28 KB level,
+//   pitch 32 KB (8192^2) 133 / 104 (SBM 150 / 116; 7x7 156 / 130), 48 KB level,
+//   pitch 64 KB (2048 x 16384) 59 / 46, (40960 x 16384) 1275 / 971,
+//   pitch 160 KB (16384 x 40960) 1320 / 1016 (2x2: 1289 / 969), pitch 2.5 MB 1117 / 1084;
+//   4 and 8 strips lie between.  Single strips win while the rows are short, bands as
+//   soon as walking down a strip strides over 32 KB or more.
+inline int band_width(size_t x_pitch) { return x_pitch * sizeof(float) >= 32768 ? 16 : 1; }
+
+// Workgroups a launch of such a kernel needs (a multiple of the XCD count) and the
+// length of an XCD's run.
+inline long long tile_workgroups(int row_blocks, int strips, long long& per_xcd)
+{
+    const long long groups = (long long)((row_blocks + (kBlock / kWave) - 1) / (kBlock / kWave)) * strips;
+    per_xcd = (groups + kXcds - 1) / kXcds;
+    return per_xcd * kXcds;
+}
+
 // ------------------------------------------------------------- FBS 2-D -----
 // Section 6.2: "FBS ... converts a 2-D convolution into multiple FBS 1-D
 // convolutions".  A workgroup stages a (32 + kh - 1) x 256 input tile in LDS
@@ -42,13 +95,14 @@ __device__ __forceinline__ void fbs_rows(float (&e)[kFbsRowsPerWave][4], float (
 __global__ __launch_bounds__(kBlock) void conv2d_fbs_kernel(const float* __restrict__ x, float* __restrict__ y,
                                                             int h, int w_img, long long xp, int oh, int ow,
                                                             long long yp, int kh, int kw, int tiles_y, int n_tiles,
-                                                            int per_xcd, Taps2D taps)
+                                                            int side, int per_xcd, Taps2D taps)
 {
     extern __shared__ __attribute__((aligned(16))) float tile[];           // (kFbsTileRows + kh - 1) x kStrip
 
     const int t = xcd_contiguous(blockIdx.x, per_xcd);
     if (t >= n_tiles) return;                                              // whole workgroup leaves together
-    const int tile_y = t % tiles_y, tile_x = t / tiles_y;                  // consecutive items go down a strip
+    int tile_y, tile_x;
+    band_order(t, tiles_y, n_tiles / tiles_y, side, tile_y, tile_x);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = wave_in_block();
     const int valid_lanes = kWave - halo_lanes(kw);
@@ -287,17 +341,13 @@ template <int KH, int KW, int PD>
 __global__ __launch_bounds__(kBlock) void conv2d_bfs_kernel(Taps2D taps, const float* __restrict__ x,
                                                             float* __restrict__ y, int w_img, long long xp, int oh,
                                                             int ow, long long yp, int rows, int row_blocks,
-                                                            int n_items, int per_xcd, int valid_lanes)
+                                                            int strips, int side, int per_xcd, int valid_lanes)
 {
     (void)taps;
     (void)valid_lanes;
     kernarg_floats taps_f = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
-    const int item = xcd_contiguous(blockIdx.x, per_xcd) * (kBlock / kWave) + wave_in_block();
-    if (item >= n_items) return;                                           // uniform per wavefront
-    // consecutive items go down a strip, and every XCD owns a contiguous run of items:
-    // the row blocks that share halo rows meet in one L2 (measured against row-major
-    // and plain round-robin orders on 4096^2, 5x5: 35 us vs 37-41 us)
-    const int rb = item % row_blocks, strip = item / row_blocks;
+    int rb, strip;
+    if (!wave_tile(per_xcd, row_blocks, strips, side, rb, strip)) return;
     const int lane = threadIdx.x & (kWave - 1);
     const int col0 = strip * kStrip;                                       // strips are 256 outputs wide
     const int r0 = rb * rows;
@@ -407,16 +457,12 @@ template <int KH, int KW, int PD>
 __global__ __launch_bounds__(kBlock) void conv2d_sbm_kernel(Taps2D taps_t, const float* __restrict__ x,
                                                             float* __restrict__ y, int w_img, long long xp, int oh,
                                                             int ow, long long yp, int rows, int row_blocks,
-                                                            int n_items, int per_xcd, int valid_lanes)
+                                                            int strips, int side, int per_xcd, int valid_lanes)
 {
     (void)taps_t;
     kernarg_floats tf = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
-    const int item = xcd_contiguous(blockIdx.x, per_xcd) * (kBlock / kWave) + wave_in_block();
-    if (item >= n_items) return;
-    // consecutive items go down a strip, and every XCD owns a contiguous run of items:
-    // the row blocks that share halo rows meet in one L2 (measured against row-major
-    // and plain round-robin orders on 4096^2, 5x5: 35 us vs 37-41 us)
-    const int rb = item % row_blocks, strip = item / row_blocks;
+    int rb, strip;
+    if (!wave_tile(per_xcd, row_blocks, strips, side, rb, strip)) return;
     const int lane = threadIdx.x & (kWave - 1);
     const int col0 = strip * kTile * valid_lanes;
     const int r0 = rb * rows;
@@ -519,13 +565,12 @@ template <int KH, int KW, int ROWS>
 __global__ __launch_bounds__(kBlock) void conv2d_bfs_block_kernel(Taps2D taps, const float* __restrict__ x,
                                                                   float* __restrict__ y, int w_img, long long xp,
                                                                   int oh, int ow, long long yp, int row_blocks,
-                                                                  int n_items, int per_xcd)
+                                                                  int strips, int side, int per_xcd)
 {
     (void)taps;
     kernarg_floats taps_f = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
-    const int item = xcd_contiguous(blockIdx.x, per_xcd) * (kBlock / kWave) + wave_in_block();
-    if (item >= n_items) return;                                           // uniform per wavefront
-    const int rb = item % row_blocks, strip = item / row_blocks;           // consecutive items go down a strip
+    int rb, strip;
+    if (!wave_tile(per_xcd, row_blocks, strips, side, rb, strip)) return;
     const int lane = threadIdx.x & (kWave - 1);
     const int col0 = strip * kStrip;
     const int r0 = rb * ROWS;
@@ -577,18 +622,16 @@ hipError_t launch_strip(const float* x, int h, int w, size_t xp, const float* f,
     int rows = SBM ? (KH <= 5 ? 4 : 8) : (KH <= 5 ? 6 : 16);
     if (rows > oh) rows = oh;
     const int row_blocks = (oh + rows - 1) / rows;
-    const long long n_items = (long long)row_blocks * strips;
-    const long long groups = (n_items + (kBlock / kWave) - 1) / (kBlock / kWave);
-    const long long per_xcd = (groups + kXcds - 1) / kXcds;
-    const long long blocks = per_xcd * kXcds;
-    if (blocks > 0x7fffffffLL || n_items > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    long long per_xcd;
+    const long long blocks = tile_workgroups(row_blocks, strips, per_xcd);
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     if constexpr (SBM)
         hipLaunchKernelGGL((conv2d_sbm_kernel<KH, KW, PD>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
-                           taps, x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, (int)n_items,
+                           taps, x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, strips, band_width(xp),
                            (int)per_xcd, valid_lanes);
     else
         hipLaunchKernelGGL((conv2d_bfs_kernel<KH, KW, PD>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
-                           taps, x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, (int)n_items,
+                           taps, x, y, w, (long long)xp, oh, ow, (long long)yp, rows, row_blocks, strips, band_width(xp),
                            (int)per_xcd, valid_lanes);
     return hipGetLastError();
 }
@@ -611,7 +654,7 @@ hipError_t launch_conv2d_fbs(const float* x, int h, int w, size_t xp, const floa
     const size_t lds = (size_t)(kFbsTileRows + kh - 1) * kStrip * sizeof(float);
     hipLaunchKernelGGL(conv2d_fbs_kernel, dim3((unsigned)blocks), dim3(kBlock), lds, s,
                        x, y, h, w, (long long)xp, oh, ow, (long long)yp, kh, kw, tiles_y, (int)n_tiles,
-                       (int)per_xcd, taps);
+                       band_width(xp), (int)per_xcd, taps);
     return hipGetLastError();
 }
 
@@ -624,13 +667,11 @@ hipError_t launch_bfs_block(const float* x, int h, int w, size_t xp, const float
     const int oh = h - KH + 1, ow = w - KW + 1;
     const int strips = (ow + kStrip - 1) / kStrip;
     const int row_blocks = (oh + ROWS - 1) / ROWS;
-    const long long n_items = (long long)row_blocks * strips;
-    const long long groups = (n_items + (kBlock / kWave) - 1) / (kBlock / kWave);
-    const long long per_xcd = (groups + kXcds - 1) / kXcds;
-    const long long blocks = per_xcd * kXcds;
-    if (blocks > 0x7fffffffLL || n_items > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    long long per_xcd;
+    const long long blocks = tile_workgroups(row_blocks, strips, per_xcd);
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL((conv2d_bfs_block_kernel<KH, KW, ROWS>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
-                       taps, x, y, w, (long long)xp, oh, ow, (long long)yp, row_blocks, (int)n_items,
+                       taps, x, y, w, (long long)xp, oh, ow, (long long)yp, row_blocks, strips, band_width(xp),
                        (int)per_xcd);
     return hipGetLastError();
 }

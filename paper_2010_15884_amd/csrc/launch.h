@@ -25,6 +25,7 @@ hipError_t launch_conv1d_sbm(const float* x, size_t n, const float* w, int k, fl
 hipError_t launch_conv1d_bsm(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s);
 hipError_t launch_conv1d_fsm(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s);
 hipError_t launch_conv1d_ffs(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s);
+hipError_t launch_conv1d_fbs_stride2(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s);
 bool has_conv1d_bfs(int k);
 hipError_t launch_conv1d_bfs(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s);
 

@@ -115,3 +115,38 @@ def test_binding_rejects_host_tensors():
     torch = pytest.importorskip("torch")
     with pytest.raises(TypeError):
         B.sys_conv1d(torch.zeros(10), np.ones(3, np.float32))
+
+
+@pytest.mark.parametrize("args,want", [
+    ((None, 100, "w", 5, 2, Y, 1), B.SYS_ERR_NULL),
+    ((X, 100, "w", 5, 2, None, 0), B.SYS_ERR_NULL),
+    ((X, 100, "w", 5, 0, Y, 1), B.SYS_ERR_SIZE),
+    ((X, 100, "w", 5, -2, Y, 1), B.SYS_ERR_SIZE),
+    ((X, 4, "w", 5, 2, Y, 1), B.SYS_ERR_SIZE),
+    ((X, 100, "w", 0, 2, Y, 1), B.SYS_ERR_SIZE),
+    ((X, 100, "w", 65, 2, Y, 1), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, "w", 5, 3, Y, 1), B.SYS_ERR_UNSUPPORTED),                  # only strides 1 and 2 are built
+    ((X, 100, "w", 5, 2, Y, B.SYS_PROJ_SBM), B.SYS_ERR_UNSUPPORTED),     # stride 2 is an FBS design only
+    ((X, 100, "w", 5, 2, Y, B.SYS_PROJ_BFS), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, "w", 5, 2, Y, 9), B.SYS_ERR_UNSUPPORTED),
+    ((X + 2, 100, "w", 5, 2, Y, 1), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, "w", 5, 2, X + 4 * 99, 0), B.SYS_ERR_ALIAS),
+    ((X + 4 * 47, 100, "w", 5, 2, X, 0), B.SYS_ERR_ALIAS),               # 48 outputs: y = [X, X+192) touches x
+    ((X, 100, "w", 5, 1, X, 1), B.SYS_ERR_ALIAS),                        # stride 1 goes through sys_conv1d's checks
+    ((X, 100, "w", 65, 1, Y, 1), B.SYS_ERR_UNSUPPORTED),
+])
+def test_conv1d_strided_validation(args, want):
+    x, n, w, k, stride, y, proj = args
+    keep, wp = _w(k)
+    got = B.lib().sys_conv1d_strided(x, n, wp if w else None, k, stride, y, proj, None)
+    assert got == want, B.status_string(got)
+
+
+def test_conv1d_strided_has():
+    for k in (1, 2, 5, 16, 64):
+        assert B.sys_conv1d_strided_has("AUTO", k, 2) and B.sys_conv1d_strided_has("FBS", k, 2)
+        for proj in ("SBM", "BFS", "BSM", "FSM", "FFS"):
+            assert not B.sys_conv1d_strided_has(proj, k, 2)
+            assert B.sys_conv1d_strided_has(proj, k, 1) == B.sys_conv1d_has(proj, k)
+        assert not B.sys_conv1d_strided_has("FBS", k, 3) and not B.sys_conv1d_strided_has("FBS", k, 0)
+    assert not B.sys_conv1d_strided_has("FBS", 65, 2) and not B.sys_conv1d_strided_has("FBS", 0, 2)

@@ -161,3 +161,19 @@ def test_2d_calls_chain_on_a_stream_without_host_sync():
             mid_h = mid.cpu().numpy()
             assert err2d(mid_h, xh, f1) <= TOL, f"{proj} round {rep} first call"
             assert err2d(out.cpu().numpy(), mid_h, f2) <= TOL, f"{proj} round {rep} second call"
+
+
+def test_binding_rejects_outputs_that_are_too_small():
+    x = torch.zeros(1000, dtype=torch.float32, device="cuda")
+    w = np.ones(5, np.float32)
+    with pytest.raises(ValueError):
+        B.sys_conv1d(x, w, torch.empty(995, dtype=torch.float32, device="cuda"))
+    with pytest.raises(ValueError):
+        B.sys_conv1d_strided(x, w, 2, torch.empty(497, dtype=torch.float32, device="cuda"))
+    with pytest.raises(ValueError):
+        B.sys_conv1d(x, w, torch.empty(2000, dtype=torch.float32, device="cuda")[::2])
+    img = torch.zeros((50, 60), dtype=torch.float32, device="cuda")
+    with pytest.raises(ValueError):
+        B.sys_conv2d(img, np.ones((3, 3), np.float32), torch.empty((48, 57), dtype=torch.float32, device="cuda"))
+    with pytest.raises(ValueError):
+        B.sys_conv2d(img, np.ones((3, 3), np.float32), torch.empty((47, 58), dtype=torch.float32, device="cuda"))
