@@ -159,6 +159,23 @@ def main() -> int:
                     p = paper_rel[proj][0 if k == 2 else 1]
                     row["paper_relative_to_FBS"] = round(p / paper_rel["FBS"][0 if k == 2 else 1], 3)
                 rows.append(row)
+            # the same six designs through the generic space-time-transform kernel (one PE per lane,
+            # nothing specialised): what the general code shape of Section 4.1 costs on this machine
+            for proj in ("FBS", "SBM", "BFS", "BSM", "FSM", "FFS"):
+                design = B.named_design(proj)
+                dxs = [torch.from_numpy(x_host).cuda() for _ in range(2)]
+                dys = [torch.empty(wk.y_shape, dtype=torch.float32, device="cuda") for _ in range(2)]
+                state = {"i": 0}
+
+                def launch():
+                    i = state["i"] = (state["i"] + 1) % 2
+                    B.sys_conv1d_stt(dxs[i], taps, design, dys[i])
+                _, k_mean, _ = time_launches(launch, 5, 1)
+                del dxs, dys
+                rows.append({"k": k, "design": f"generic({proj})", "kernel_us": round(k_mean * 1e6, 1),
+                             "GB/s": round(wk.algorithmic_bytes / k_mean / 1e9, 1),
+                             "Gtap/s": round(wk.n_taps / k_mean / 1e9, 1),
+                             "relative_to_FBS": round(t_fbs / k_mean, 3)})
         print(json.dumps({"design_space_1d": rows, "n": wl.x_shape[0], "data": "synthetic",
                           "note": "paper column: Table 3 (Intel GEN9.5, relative to its hardware sampler), "
                                   "rescaled to FBS = 1; context, not a target"}))

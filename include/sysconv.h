@@ -72,7 +72,9 @@ typedef enum {
     SYS_ERR_ALIAS = 3,        /* input and output byte ranges overlap                */
     SYS_ERR_UNSUPPORTED = 4,  /* size beyond the limits below / unknown projection /
                                  projection not built for this filter size          */
-    SYS_ERR_HIP = 5           /* a HIP call failed; see sys_last_hip_error()         */
+    SYS_ERR_HIP = 5,          /* a HIP call failed; see sys_last_hip_error()         */
+    SYS_ERR_DESIGN = 6        /* a space-time design breaks the recurrences or the
+                                 conditions of Section 2.2 (see sys_stt_check)       */
 } sys_status_t;
 
 typedef enum {
@@ -120,6 +122,59 @@ int sys_conv1d_strided(const float *d_x, size_t n,
 
 /* 1 if sys_conv1d_strided(projection) is built for a k-tap filter at this stride, else 0. */
 int sys_conv1d_strided_has(int projection, int k, int stride);
+
+/*
+ * A 1-D systolic design in the paper's terms (Section 2.2, Section 3.1, Table 2) over the
+ * iteration space z = (c, q), output position c and tap q:
+ *   alloc  P:  processing element  = alloc[0]*c + alloc[1]*q
+ *   sched  s:  time step           = sched[0]*c + sched[1]*q
+ *   X, the input x(c+q): loaded by every PE that needs it (x_passed = 0), or handed on,
+ *      X(z) = X(z - dep_x) wherever z - dep_x lies in the PE array's chunk of outputs;
+ *      dep_x = (a, -a), a != 0, since both points must read the same input.
+ *   W, the tap w(q): w_passed = 0, or W(z) = W(z - dep_w) with dep_w = (a, 0), a != 0.
+ *   Z, the partial sum: Z(z) = Z(z - dep_z) + X(z)*W(z), dep_z = (0, 1) (taps ascending)
+ *      or (0, -1) (descending); the output leaves where that chain ends.
+ * SBM is {P=(1,1), s=(0,1), dep_x=(-1,1), W loaded, dep_z=(0,1)}; the rows of Table 2 are
+ * written the same way.
+ */
+typedef struct {
+    int alloc[2];
+    int sched[2];
+    int x_passed;
+    int dep_x[2];
+    int w_passed;
+    int dep_w[2];
+    int dep_z[2];
+} sys_stt_design_t;
+
+/*
+ * Check a design for a k-tap filter without running anything:
+ *   SYS_OK               it can be run by sys_conv1d_stt
+ *   SYS_ERR_DESIGN       it is not a valid systolic design: a dependence vector does not
+ *                        fit the recurrences above, the transform is singular (two
+ *                        iteration points on one PE at one time), or a passed value
+ *                        would be needed before it exists (s.e < 1; Section 2.2)
+ *   SYS_ERR_UNSUPPORTED  valid, but beyond this kernel: |det(P; s)| != 1, a value that
+ *                        travels more than one PE per hand-over (|P.e| > 1) or more than
+ *                        3 time steps (s.e > 3), coefficients beyond +-64, or a PE vector
+ *                        that does not fit 64 lanes for this k
+ *   SYS_ERR_NULL / SYS_ERR_SIZE  design == NULL / k outside 1..SYS_MAX_K1D
+ */
+int sys_stt_check(const sys_stt_design_t *design, int k);
+
+/*
+ * 1-D valid convolution (Eq. 2, as sys_conv1d) executed by the general form of the
+ * paper's generated code (Section 4.1) for the given design: one PE per lane, per-PE
+ * histories as deep as each variable's time distance, the transform inverted at every
+ * step.  Every design that passes sys_stt_check gives the result of sys_conv1d to
+ * rounding; it runs several times slower than the hand-laid projections and exists to
+ * try designs, not to serve them.  Arguments and errors as sys_conv1d, plus those of
+ * sys_stt_check.
+ */
+int sys_conv1d_stt(const float *d_x, size_t n,
+                   const float *h_w, int k,
+                   float *d_y,
+                   const sys_stt_design_t *design, hipStream_t stream);
 
 /*
  * 2-D valid convolution, Eq. 3, single channel, row-major:

@@ -20,14 +20,43 @@ SYS_OK, SYS_ERR_NULL, SYS_ERR_SIZE, SYS_ERR_ALIAS, SYS_ERR_UNSUPPORTED, SYS_ERR_
 SYS_PROJ_AUTO, SYS_PROJ_FBS, SYS_PROJ_BFS, SYS_PROJ_SBM, SYS_PROJ_BSM, SYS_PROJ_FSM, SYS_PROJ_FFS = range(7)
 PROJECTIONS = {"AUTO": SYS_PROJ_AUTO, "FBS": SYS_PROJ_FBS, "BFS": SYS_PROJ_BFS, "SBM": SYS_PROJ_SBM,
                "BSM": SYS_PROJ_BSM, "FSM": SYS_PROJ_FSM, "FFS": SYS_PROJ_FFS}
+SYS_ERR_DESIGN = 6
 SYS_MAX_K1D = 64
 SYS_MAX_K2D = 15
 
 EXPORTS = ["sys_conv1d", "sys_conv1d_strided", "sys_conv2d", "sys_conv1d_has", "sys_conv1d_strided_has",
-           "sys_conv2d_has", "sys_copy_f32", "sys_status_string",
+           "sys_conv2d_has", "sys_stt_check", "sys_conv1d_stt", "sys_copy_f32", "sys_status_string",
            "sys_projection_name", "sys_last_hip_error", "sys_version"]
 
 _lib = None
+
+
+class SttDesign(ctypes.Structure):
+    """sys_stt_design_t: transform rows P and s over (c, q) and the dependence vectors of X, W, Z."""
+    _fields_ = [("alloc", ctypes.c_int * 2), ("sched", ctypes.c_int * 2),
+                ("x_passed", ctypes.c_int), ("dep_x", ctypes.c_int * 2),
+                ("w_passed", ctypes.c_int), ("dep_w", ctypes.c_int * 2),
+                ("dep_z", ctypes.c_int * 2)]
+
+
+def stt_design(alloc, sched, dep_x=None, dep_w=None, dep_z=(0, 1)) -> SttDesign:
+    """Build a design; ``dep_x`` / ``dep_w`` = None means the variable is loaded by every PE."""
+    d = SttDesign()
+    d.alloc[:] = [int(v) for v in alloc]
+    d.sched[:] = [int(v) for v in sched]
+    d.x_passed = int(dep_x is not None)
+    d.dep_x[:] = [int(v) for v in (dep_x or (0, 0))]
+    d.w_passed = int(dep_w is not None)
+    d.dep_w[:] = [int(v) for v in (dep_w or (0, 0))]
+    d.dep_z[:] = [int(v) for v in dep_z]
+    return d
+
+
+def named_design(name: str) -> SttDesign:
+    """One of the paper's six designs (Section 3.1, Table 2) as a sys_stt_design_t."""
+    from . import schedule_model as sm
+    t, e = sm.TRANSFORMS[name], sm.DEPENDENCES[name]
+    return stt_design(t.alloc, t.sched, e.get("X"), e.get("W"), e["Z"])
 
 
 class SysconvError(RuntimeError):
@@ -59,6 +88,10 @@ def lib() -> ctypes.CDLL:
         L.sys_conv1d_strided.restype = ci
         L.sys_conv1d_strided_has.argtypes = [ci, ci, ci]
         L.sys_conv1d_strided_has.restype = ci
+        L.sys_stt_check.argtypes = [ctypes.POINTER(SttDesign), ci]
+        L.sys_stt_check.restype = ci
+        L.sys_conv1d_stt.argtypes = [vp, sz, fp, ci, vp, ctypes.POINTER(SttDesign), vp]
+        L.sys_conv1d_stt.restype = ci
         L.sys_conv1d_has.argtypes = [ci, ci]
         L.sys_conv1d_has.restype = ci
         L.sys_conv2d_has.argtypes = [ci, ci, ci]
@@ -155,6 +188,27 @@ def sys_conv1d_strided(d_x, h_w, stride, d_y=None, projection="AUTO", stream=Non
     _room_1d(d_y, m)
     _check(lib().sys_conv1d_strided(d_x.data_ptr(), n, w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), k, stride,
                                     d_y.data_ptr(), _proj(projection), _stream_handle(stream)))
+    return d_y
+
+
+def sys_stt_check(design: SttDesign, k: int) -> int:
+    """Status the library gives this design for a k-tap filter (SYS_OK, SYS_ERR_DESIGN, ...)."""
+    return int(lib().sys_stt_check(ctypes.byref(design), int(k)))
+
+
+def sys_conv1d_stt(d_x, h_w, design: SttDesign, d_y=None, stream=None):
+    """sys_conv1d computed by the generic space-time-transform kernel for ``design``."""
+    import torch
+    _device_f32(d_x, "d_x")
+    if d_x.dim() != 1 or not d_x.is_contiguous():
+        raise ValueError("d_x must be a contiguous 1-D tensor")
+    w = _taps(h_w)
+    n, k = d_x.shape[0], w.shape[0]
+    if d_y is None:
+        d_y = torch.empty(max(n - k + 1, 0), dtype=torch.float32, device=d_x.device)
+    _room_1d(d_y, max(n - k + 1, 0))
+    _check(lib().sys_conv1d_stt(d_x.data_ptr(), n, w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), k,
+                                d_y.data_ptr(), ctypes.byref(design), _stream_handle(stream)))
     return d_y
 
 

@@ -86,6 +86,41 @@ int sys_conv1d_strided_has(int projection, int k, int stride)
     return (projection == SYS_PROJ_AUTO || projection == SYS_PROJ_FBS) ? 1 : 0;
 }
 
+namespace {
+int stt_status(const sys_stt_design_t* d, int k, sysconv::SttPlan* plan)
+{
+    if (!d) return SYS_ERR_NULL;
+    if (k < 1 || k > SYS_MAX_K1D) return SYS_ERR_SIZE;
+    switch (sysconv::plan_stt(d->alloc, d->sched, d->x_passed != 0, d->dep_x, d->w_passed != 0, d->dep_w, d->dep_z, k,
+                              plan)) {
+    case sysconv::kSttOk: return SYS_OK;
+    case sysconv::kSttTooLarge: return SYS_ERR_UNSUPPORTED;
+    default: return SYS_ERR_DESIGN;
+    }
+}
+}  // namespace
+
+int sys_stt_check(const sys_stt_design_t* design, int k)
+{
+    return stt_status(design, k, nullptr);
+}
+
+int sys_conv1d_stt(const float* d_x, size_t n, const float* h_w, int k, float* d_y, const sys_stt_design_t* design,
+                   hipStream_t stream)
+{
+    if (!d_x || !h_w || !d_y || !design) return SYS_ERR_NULL;
+    if (k < 1 || (size_t)k > n) return SYS_ERR_SIZE;
+    if (k > SYS_MAX_K1D) return SYS_ERR_UNSUPPORTED;
+    sysconv::SttPlan plan;
+    const int st = stt_status(design, k, &plan);
+    if (st != SYS_OK) return st;
+    if (misaligned(d_x) || misaligned(d_y)) return SYS_ERR_UNSUPPORTED;
+    if (n > ((size_t)1 << 40)) return SYS_ERR_UNSUPPORTED;
+    const size_t m = n - (size_t)k + 1;
+    if (ranges_overlap(d_x, n * sizeof(float), d_y, m * sizeof(float))) return SYS_ERR_ALIAS;
+    return hip_status(sysconv::launch_conv1d_stt(d_x, n, h_w, k, d_y, plan, stream));
+}
+
 int sys_conv1d_has(int projection, int k)
 {
     if (k < 1 || k > SYS_MAX_K1D) return 0;
@@ -164,6 +199,7 @@ const char* sys_status_string(int status)
     case SYS_ERR_ALIAS: return "input and output ranges overlap";
     case SYS_ERR_UNSUPPORTED: return "unsupported size, alignment or projection";
     case SYS_ERR_HIP: return "HIP runtime error (see sys_last_hip_error)";
+    case SYS_ERR_DESIGN: return "not a valid systolic design (dependence, singular transform or causality)";
     default: return "unknown status";
     }
 }

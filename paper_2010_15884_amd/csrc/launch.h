@@ -29,6 +29,30 @@ hipError_t launch_conv1d_fbs_stride2(const float* x, size_t n, const float* w, i
 bool has_conv1d_bfs(int k);
 hipError_t launch_conv1d_bfs(const float* x, size_t n, const float* w, int k, float* y, hipStream_t s);
 
+// Generic space-time-transform kernel (conv1d_stt.hip).  A plan is what the host derives
+// from a design: the transform, its inverse's sign, the chunk of outputs one wavefront
+// takes, the lowest PE / time coordinates, and per passed variable its dependence and
+// the space (dl = P.e) and time (dt = s.e) distance it travels.
+constexpr int kSttDepth = 3;                  // longest time distance a passed value may travel
+struct SttPlan {
+    int p0, p1, s0, s1, det;
+    int chunk, pe_min, time_min, steps;
+    int x_on, x_ec, x_eq, x_dl, x_dt;
+    int w_on, w_ec, w_dl, w_dt;
+    int z_eq, z_dl, z_dt;
+};
+enum SttVerdict {
+    kSttOk = 0,
+    kSttBadDependence,        // a dependence vector does not fit the convolution recurrences
+    kSttSingular,             // det(P; s) = 0: two iteration points on one PE at one time
+    kSttNotCausal,            // s.e < 1 for a passed variable
+    kSttTooLarge              // valid, but outside what the kernel is built for
+};
+SttVerdict plan_stt(const int alloc[2], const int sched[2], bool x_on, const int ex[2], bool w_on, const int ew[2],
+                    const int ez[2], int k, SttPlan* out);
+hipError_t launch_conv1d_stt(const float* x, size_t n, const float* w, int k, float* y, const SttPlan& plan,
+                             hipStream_t s);
+
 hipError_t launch_conv2d_fbs(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
                              float* y, size_t yp, hipStream_t s);
 bool has_conv2d_bfs(int kh, int kw);

@@ -105,3 +105,74 @@ def ffs_wave(x, w, width=16):
         z = np.where(valid, z + xt * wt, z)
         w2, w1 = w1, wt
     return z[: arrays * width]
+
+
+# ------------------------------------------------------------------ generic space-time transform
+def stt_plan(alloc, sched, dep_x, dep_w, dep_z, k, lanes=LANES):
+    """Host-side bookkeeping of the generic kernel for one wavefront: outputs per chunk C, the lowest
+    PE and time coordinates, the number of steps, and (lane distance, time distance) per variable.
+    Mirrors Section 2.2 / Section 4.1: PE = P.z, time = s.z, a value passed along e travels P.e PEs
+    in s.e steps."""
+    p0, p1 = alloc
+    s0, s1 = sched
+    det = p0 * s1 - p1 * s0
+    assert det in (1, -1)
+    C = lanes if p0 == 0 else (lanes - 1 - abs(p1) * (k - 1)) // abs(p0) + 1
+    C = min(C, lanes)
+    assert C >= 1
+    pmin = min(0, p0 * (C - 1)) + min(0, p1 * (k - 1))
+    tmin = min(0, s0 * (C - 1)) + min(0, s1 * (k - 1))
+    steps = abs(s0) * (C - 1) + abs(s1) * (k - 1) + 1
+    dist = {}
+    for name, e in (("X", dep_x), ("W", dep_w), ("Z", dep_z)):
+        dist[name] = None if e is None else (p0 * e[0] + p1 * e[1], s0 * e[0] + s1 * e[1])
+    return dict(det=det, C=C, pmin=pmin, tmin=tmin, steps=steps, dist=dist)
+
+
+def stt_wave(alloc, sched, dep_x, dep_w, dep_z, x, w, lanes=LANES):
+    """One wavefront of the generic kernel: every lane is a PE; per time step each lane inverts the
+    transform to find its iteration point (c, q), takes X / W / Z either from memory (no dependence, or
+    the producer z - e lies outside the chunk) or from its neighbour's history, and multiplies-adds.
+    Returns the outputs of the first chunk (min(C, len(x)-k+1) of them)."""
+    x = np.asarray(x, np.float64)
+    w = np.asarray(w, np.float64)
+    k = len(w)
+    pl = stt_plan(alloc, sched, dep_x, dep_w, dep_z, k, lanes)
+    p0, p1 = alloc
+    s0, s1 = sched
+    det, C = pl["det"], pl["C"]
+    Cv = min(C, len(x) - k + 1)                                  # outputs that exist in this chunk
+    lane = np.arange(lanes)
+    hist = {v: [np.zeros(lanes) for _ in range(3)] for v in "XWZ"}
+    y = np.full(Cv, np.nan)
+
+    def moved(var):
+        dl, dt = pl["dist"][var]
+        v = hist[var][dt - 1]                                    # produced dt steps ago ...
+        if dl == 1:
+            return _below(v)                                     # ... by the PE one below
+        if dl == -1:
+            return _above(v)
+        return v
+
+    for t in range(pl["steps"]):
+        pp, tp = lane + pl["pmin"], t + pl["tmin"]
+        c = det * (s1 * pp - p1 * tp)
+        q = det * (-s0 * pp + p0 * tp)
+        valid = (c >= 0) & (c < Cv) & (q >= 0) & (q < k)
+        xin = x[np.clip(c + q, 0, len(x) - 1)]
+        win = w[np.clip(q, 0, k - 1)]
+
+        def inside(e):
+            cc, qq = c - e[0], q - e[1]
+            return (cc >= 0) & (cc < Cv) & (qq >= 0) & (qq < k)
+
+        xv = xin if dep_x is None else np.where(inside(dep_x), moved("X"), xin)
+        wv = win if dep_w is None else np.where(inside(dep_w), moved("W"), win)
+        zv = np.where(inside(dep_z), moved("Z"), 0.0) + xv * wv
+        last = valid & ~(((q + dep_z[1]) >= 0) & ((q + dep_z[1]) < k))
+        for l in np.nonzero(last)[0]:
+            y[c[l]] = zv[l]
+        for var, val in (("X", xv), ("W", wv), ("Z", zv)):
+            hist[var] = [val, hist[var][0], hist[var][1]]
+    return y
