@@ -5,9 +5,10 @@
  *       -L paper_2010_15884_amd -lsysconv -L/opt/rocm/lib -lamdhip64 -lm \
  *       -Wl,-rpath,$PWD/paper_2010_15884_amd -Wl,-rpath,/opt/rocm/lib -o c_abi_demo && ./c_abi_demo
  *
- * Runs y = conv1d(x, w) and a 5x5 conv2d in every projection on small ramps whose
- * results have closed forms (x[i] = i  =>  y[i] = i*sum(w) + sum(k*w[k])), checks them,
- * and shows the error paths.  Exit status 0 = all good.
+ * Runs y = conv1d(x, w) in every projection, at stride 2, and through the generic
+ * space-time-transform kernel with a design written down as data; a 5x5 conv2d in every
+ * projection; checks everything against sums computed here, and shows the error paths.
+ * Exit status 0 = all good.
  */
 #include <math.h>
 #include <stdio.h>
@@ -36,7 +37,7 @@ int main(void)
     CHECK_HIP(hipMemcpy(dx, hx, n * sizeof(float), hipMemcpyHostToDevice));
 
     int failures = 0;
-    for (int proj = SYS_PROJ_AUTO; proj <= SYS_PROJ_SBM; ++proj) {
+    for (int proj = SYS_PROJ_AUTO; proj <= SYS_PROJ_FFS; ++proj) {
         if (!sys_conv1d_has(proj, k)) continue;
         int st = sys_conv1d(dx, n, w, k, dy, proj, 0);
         if (st != SYS_OK) { fprintf(stderr, "conv1d %s: %s\n", sys_projection_name(proj), sys_status_string(st)); return 3; }
@@ -51,6 +52,42 @@ int main(void)
         }
         printf("conv1d %-4s n=%zu k=%d: max abs err %.3g\n", sys_projection_name(proj), n, k, worst);
         if (worst > 0.05) ++failures;                               /* values reach ~6000: 1e-5 relative */
+    }
+
+    /* stride 2 (FBS only), and a design given as data to the generic kernel: SBM whose
+     * partial sums move every second step (PE = c + q, time = c + 2q), which no table lists */
+    {
+        const size_t m2 = (n - k) / 2 + 1;
+        int st = sys_conv1d_strided(dx, n, w, k, 2, dy, SYS_PROJ_FBS, 0);
+        if (st != SYS_OK) { fprintf(stderr, "stride 2: %s\n", sys_status_string(st)); return 3; }
+        CHECK_HIP(hipDeviceSynchronize());
+        CHECK_HIP(hipMemcpy(hy, dy, m2 * sizeof(float), hipMemcpyDeviceToHost));
+        double worst = 0;
+        for (size_t c = 0; c < m2; ++c) {
+            double ref = 0;
+            for (int q = 0; q < k; ++q) ref += (double)w[q] * hx[2 * c + q];
+            if (fabs(hy[c] - ref) > worst) worst = fabs(hy[c] - ref);
+        }
+        printf("conv1d FBS stride 2, %zu outputs: max abs err %.3g\n", m2, worst);
+        if (worst > 0.05) ++failures;
+
+        const sys_stt_design_t half_speed_sbm = {{1, 1}, {1, 2}, 1, {-1, 1}, 0, {0, 0}, {0, 1}};
+        const sys_stt_design_t singular = {{1, 1}, {1, 1}, 0, {0, 0}, 0, {0, 0}, {0, 1}};
+        printf("half-speed SBM  -> %s\n", sys_status_string(sys_stt_check(&half_speed_sbm, k)));
+        printf("singular design -> %s\n", sys_status_string(sys_stt_check(&singular, k)));
+        failures += sys_stt_check(&singular, k) != SYS_ERR_DESIGN;
+        st = sys_conv1d_stt(dx, n, w, k, dy, &half_speed_sbm, 0);
+        if (st != SYS_OK) { fprintf(stderr, "generic kernel: %s\n", sys_status_string(st)); return 3; }
+        CHECK_HIP(hipDeviceSynchronize());
+        CHECK_HIP(hipMemcpy(hy, dy, (n - k + 1) * sizeof(float), hipMemcpyDeviceToHost));
+        worst = 0;
+        for (size_t i = 0; i + k <= n; ++i) {
+            double ref = 0;
+            for (int q = 0; q < k; ++q) ref += (double)w[q] * hx[i + q];
+            if (fabs(hy[i] - ref) > worst) worst = fabs(hy[i] - ref);
+        }
+        printf("conv1d generic kernel, half-speed SBM: max abs err %.3g\n", worst);
+        if (worst > 0.05) ++failures;
     }
 
     /* 2-D: 300 x 500 image x[r][c] = r + 2c, 5x5 box filter => y = 25*(r + 2c) + sum(p + 2q) = ... + 150 */
