@@ -616,10 +616,14 @@ hipError_t launch_strip(const float* x, int h, int w, size_t xp, const float* f,
     // bound by the VALUs and lose to the tail of a coarse decomposition (8192^2, 11x11,
     // SBM: 246 us with 8 rows, 266 us with 24, 317 us with 64).  BFS pays KH(KH-1)/2
     // skipped filter-row blocks per item, so its items are a little taller.  The price
-    // is halo traffic: an item re-reads KH-1 input rows; for 5x5 most of those re-reads
-    // hit in cache (HBM reads 1.14x the image), for 11x11 they do not (2.1x) -- harmless
-    // there, the kernel is bound by the VALUs and moves 3.3 TB/s.
+    // is halo traffic: an item re-reads KH-1 input rows; most of those re-reads hit in
+    // cache (HBM reads 1.12x the image for 5x5, 1.6x for 11x11, which is bound by the
+    // VALUs anyway).
     int rows = SBM ? (KH <= 5 ? 4 : 8) : (KH <= 5 ? 6 : 16);
+    // Images too small to give the machine 4096 items of that height get shorter ones
+    // (1024^2, 11x11: SBM 18.4 -> 12.4 us, BFS 43.9 -> 16.4 us; 2048^2, 11x11: 31 -> 25 us,
+    // 44 -> 32 us; asking for 8192 or 16384 items instead costs up to 28 % elsewhere).
+    while (rows > 2 && (long long)((oh + rows - 1) / rows) * strips < 4096) rows = (rows + 1) / 2;
     if (rows > oh) rows = oh;
     const int row_blocks = (oh + rows - 1) / rows;
     long long per_xcd;

@@ -117,6 +117,21 @@ def test_conv2d_random_all_sizes(kshape):
             assert e <= TOL, f"{proj} {kh}x{kw} image {h}x{w}: rel err {e}"
 
 
+@pytest.mark.parametrize("kk", [2, 3, 5, 6, 7, 8, 9, 11])
+def test_conv2d_tall_images_cover_every_item_height(kk):
+    # The strip kernels give a wavefront 2 ... 16 output rows, fewer on images that would not yield 4096
+    # items otherwise.  Tall, narrow images (one strip) with 2, 4, 8 and 16 times 4096 rows (+ a ragged
+    # rest) make every height run, ring wrap-around and last short item included.
+    for mult in (2, 4, 8, 16):
+        oh, ow = mult * 4096 + 5, 37
+        h, w = oh + kk - 1, ow + kk - 1
+        x, f = W.random_case(mult * 100 + kk, (h, w), (kk, kk), x_range=(0.0, 1.0))
+        for proj in ("BFS", "SBM"):
+            y = run2d(x, f, proj)
+            e = err2d(y, x, f)
+            assert e <= TOL, f"{proj} {kk}x{kk} image {h}x{w}: rel err {e}"
+
+
 @pytest.mark.parametrize("kshape", [(2, 2), (3, 3), (5, 5), (11, 11), (4, 6)])
 def test_conv2d_integer_data_is_bit_exact(kshape):
     kh, kw = kshape
