@@ -75,29 +75,29 @@ inline long long tile_workgroups(int row_blocks, int strips, long long& per_xcd)
 
 // ------------------------------------------------------------- FBS 2-D -----
 // Section 6.2: "FBS ... converts a 2-D convolution into multiple FBS 1-D
-// convolutions".  A workgroup stages a (32 + kh - 1) x 256 input tile in LDS
-// once; each of its four wavefronts then owns eight output rows (eight
-// independent partial-sum vectors) and, for every filter row p, re-reads the
-// input rows r+p from LDS and runs the 1-D FBS time loop over q on them.
+// convolutions".  A workgroup stages a (4*RPW + kh - 1) x 256 input tile in LDS
+// once; each of its four wavefronts then owns RPW output rows (RPW independent
+// partial-sum vectors; RPW = 3, or 2 for tall filters) and, for every filter row p,
+// re-reads the input rows r+p from LDS and runs the 1-D FBS time loop over q on them.
 // Filter sizes are run-time values.
-constexpr int kFbsRowsPerWave = 8;
-constexpr int kFbsTileRows = kFbsRowsPerWave * (kBlock / kWave);          // 32 output rows per workgroup
 constexpr int kStrip = kWave * kTile;                                      // 256 input columns
 
-template <int NT, bool MORE>
-__device__ __forceinline__ void fbs_rows(float (&e)[kFbsRowsPerWave][4], float (&acc)[kFbsRowsPerWave][4],
-                                         const float (&w)[4])
+template <int NT, bool MORE, int RPW>
+__device__ __forceinline__ void fbs_rows(float (&e)[RPW][4], float (&acc)[RPW][4], const float (&w)[4])
 {
 #pragma unroll
-    for (int j = 0; j < kFbsRowsPerWave; ++j) fbs_steps<NT, MORE>(e[j], acc[j], w);
+    for (int j = 0; j < RPW; ++j) fbs_steps<NT, MORE>(e[j], acc[j], w);
 }
 
+template <int RPW>
 __global__ __launch_bounds__(kBlock) void conv2d_fbs_kernel(const float* __restrict__ x, float* __restrict__ y,
                                                             int h, int w_img, long long xp, int oh, int ow,
                                                             long long yp, int kh, int kw, int tiles_y, int n_tiles,
                                                             int side, int per_xcd, Taps2D taps)
 {
     extern __shared__ __attribute__((aligned(16))) float tile[];           // (kFbsTileRows + kh - 1) x kStrip
+    constexpr int kFbsRowsPerWave = RPW;
+    constexpr int kFbsTileRows = RPW * (kBlock / kWave);                   // output rows per workgroup
 
     const int t = xcd_contiguous(blockIdx.x, per_xcd);
     if (t >= n_tiles) return;                                              // whole workgroup leaves together
@@ -142,14 +142,14 @@ __global__ __launch_bounds__(kBlock) void conv2d_fbs_kernel(const float* __restr
 #pragma nounroll
         for (; q + 4 < kw; q += 4) {
             const float w[4] = {fp[q], fp[q + 1], fp[q + 2], fp[q + 3]};
-            fbs_rows<4, true>(e, acc, w);
+            fbs_rows<4, true, RPW>(e, acc, w);
         }
         const float w[4] = {fp[q], fp[q + 1], fp[q + 2], fp[q + 3]};
         switch (kw - q) {
-        case 4: fbs_rows<4, false>(e, acc, w); break;
-        case 3: fbs_rows<3, false>(e, acc, w); break;
-        case 2: fbs_rows<2, false>(e, acc, w); break;
-        default: fbs_rows<1, false>(e, acc, w); break;
+        case 4: fbs_rows<4, false, RPW>(e, acc, w); break;
+        case 3: fbs_rows<3, false, RPW>(e, acc, w); break;
+        case 2: fbs_rows<2, false, RPW>(e, acc, w); break;
+        default: fbs_rows<1, false, RPW>(e, acc, w); break;
         }
     }
 
@@ -642,24 +642,41 @@ hipError_t launch_strip(const float* x, int h, int w, size_t xp, const float* f,
 
 }  // namespace
 
-hipError_t launch_conv2d_fbs(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
-                             float* y, size_t yp, hipStream_t s)
+namespace {
+template <int RPW>
+hipError_t launch_fbs_tiles(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw, float* y,
+                            size_t yp, hipStream_t s)
 {
+    constexpr int tile_rows = RPW * (kBlock / kWave);
     Taps2D taps;
     fill_taps(taps, f, kh * kw);
     const int oh = h - kh + 1, ow = w - kw + 1;
     const int cols = kTile * (kWave - halo_lanes(kw));
     const int tiles_x = (ow + cols - 1) / cols;
-    const int tiles_y = (oh + kFbsTileRows - 1) / kFbsTileRows;
+    const int tiles_y = (oh + tile_rows - 1) / tile_rows;
     const long long n_tiles = (long long)tiles_x * tiles_y;
     const long long per_xcd = (n_tiles + kXcds - 1) / kXcds;
     const long long blocks = per_xcd * kXcds;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    const size_t lds = (size_t)(kFbsTileRows + kh - 1) * kStrip * sizeof(float);
-    hipLaunchKernelGGL(conv2d_fbs_kernel, dim3((unsigned)blocks), dim3(kBlock), lds, s,
+    const size_t lds = (size_t)(tile_rows + kh - 1) * kStrip * sizeof(float);
+    hipLaunchKernelGGL(conv2d_fbs_kernel<RPW>, dim3((unsigned)blocks), dim3(kBlock), lds, s,
                        x, y, h, w, (long long)xp, oh, ow, (long long)yp, kh, kw, tiles_y, (int)n_tiles,
                        band_width(xp), (int)per_xcd, taps);
     return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_conv2d_fbs(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
+                             float* y, size_t yp, hipStream_t s)
+{
+    // Output rows per wavefront, measured on MI355X with 1, 2, 3, 4, 6 and 8 (us):
+    //   4096^2 5x5   50.7  38.6  34.9  36.9  39.8  43.5      8192^2 5x5    178  127  122  121  125  134
+    //   4096^2 7x7   63.3  50.1  48.6  49.9  53.3   -        8192^2 11x11  374  313  313  313  334  349
+    //   8000^2 15x15  565   532   540   541   580  603       4096^2 3x3   38.6 33.6 33.2 34.0 33.6   -
+    // Short tiles keep the LDS footprint small (more workgroups per CU); below two rows
+    // the halo rows staged per tile dominate.
+    if (kh <= 8) return launch_fbs_tiles<3>(x, h, w, xp, f, kh, kw, y, yp, s);
+    return launch_fbs_tiles<2>(x, h, w, xp, f, kh, kw, y, yp, s);
 }
 
 template <int KH, int KW, int ROWS>
