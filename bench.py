@@ -338,21 +338,29 @@ def main() -> int:
     if not args.no_cpu:
         import oracle
         threads = oracle.threads_used(min(16, os.cpu_count() or 1))
-        t0 = time.perf_counter()
-        oracle.conv1d(x_host, taps, threads)
-        cpu_s = time.perf_counter() - t0
-        t0 = time.perf_counter()
-        n1 = 1 << 24
-        oracle.conv1d(x_host[:n1], taps, 1)
-        cpu1_s = time.perf_counter() - t0
+
+        def passes(nthreads, budget_s):
+            """Whole passes of the headline workload through the oracle for about budget_s seconds."""
+            oracle.conv1d(x_host, taps, nthreads)                       # first touch of the library and the pages
+            reps, t0 = 0, time.perf_counter()
+            while True:
+                oracle.conv1d(x_host, taps, nthreads)
+                reps += 1
+                el = time.perf_counter() - t0
+                if el >= budget_s or reps >= 200:
+                    return reps, el
+
+        reps, cpu_s = passes(threads, 2.0)                              # ~30 core-seconds of CPU work
+        reps1, cpu1_s = passes(1, 2.0)
         result["cpu_baseline"] = {
-            "value": round(wl.algorithmic_bytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": threads,
+            "value": round(reps * wl.algorithmic_bytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": threads,
             "kind": "oracle",
-            "sample": f"the whole {HEADLINE} workload once ({wl.n_taps / 1e9:.2f} G fp64 multiply-adds), "
-                      f"oracle/conv_oracle.c with {threads} OpenMP threads",
+            "sample": f"{reps} passes of the whole {HEADLINE} workload ({wl.n_taps / 1e9:.2f} G fp64 multiply-adds "
+                      f"each), oracle/conv_oracle.c with {threads} OpenMP threads, result array allocated per pass",
             "seconds": round(cpu_s, 3),
-            "single_thread": {"value": round(4 * (2 * n1 - 15 + 16) / cpu1_s / 1e9, 3), "unit": "GB/s", "cores": 1,
-                              "sample": "first 2^24 inputs of the same workload", "seconds": round(cpu1_s, 3)},
+            "single_thread": {"value": round(reps1 * wl.algorithmic_bytes / cpu1_s / 1e9, 3), "unit": "GB/s",
+                              "cores": 1, "sample": f"{reps1} passes of the same workload on one thread",
+                              "seconds": round(cpu1_s, 3)},
         }
 
     print(json.dumps(result))
