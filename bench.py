@@ -269,6 +269,11 @@ def main() -> int:
     del srcs, dsts
     torch.cuda.empty_cache()
 
+    # the kernel behind the headline projection (AUTO picks FBS at 16 taps)
+    head_proj = "FBS" if args.projection.upper() == "AUTO" else args.projection.upper()
+    head_kernel = {"FBS": "conv1d_fbs_kernel<16>", "SBM": "conv1d_sbm_kernel<16>", "BFS": "conv1d_bfs_kernel<16>",
+                   "BSM": "conv1d_array_kernel<0>", "FSM": "conv1d_array_kernel<1>",
+                   "FFS": "conv1d_array_kernel<2>"}[head_proj]
     result = {
         "metric": "conv GB/s (algorithmic bytes / time), 1-D valid convolution n=2^26 K=16 fp32",
         "value": round(value, 1),
@@ -287,8 +292,8 @@ def main() -> int:
                    "gtap_per_s": round(wl.n_taps / (wall / args.steps) / 1e9, 1)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": _stored_traffic("conv1d_fbs_k16_n64m"),
-                     "kernel": "conv1d_fbs_kernel<16>", "kernel_us_mean": round(kern_mean * 1e6, 2),
+                     "traffic": _stored_traffic(f"conv1d_{head_proj.lower()}_k16_n64m"),
+                     "kernel": head_kernel, "kernel_us_mean": round(kern_mean * 1e6, 2),
                      "kernel_us_median": round(kern_med * 1e6, 2),
                      "copy_same_footprint_GB/s": round(copy_gbs, 1),
                      "frac_of_copy": round(achieved / copy_gbs, 3)},
@@ -331,7 +336,6 @@ def main() -> int:
                              "copy_GB/s_same_footprint": round(copy_gbs, 1),
                              "frac_of_copy": round(gbs / copy_gbs, 3)})
                 del ln, kp
-                pass
         result["also"] = also
 
     # ---------------------------------------------------------- CPU baseline
