@@ -48,9 +48,14 @@ int sys_conv1d(const float* d_x, size_t n, const float* h_w, int k, float* d_y, 
 
     switch (projection) {
     case SYS_PROJ_AUTO:
-        // long filters are bound by the VALUs, where BFS issues the fewest instructions
-        // (n = 2^26: k = 48: 122 us against 158 us for FBS; below k = 33 all sit on the copy rate)
-        if (k >= 36) return hip_status(sysconv::launch_conv1d_bfs(d_x, n, h_w, k, d_y, stream));
+        // Long filters are bound by the VALUs, where BFS issues the fewest instructions
+        // (n = 2^26: k = 34: 110 / 109 us FBS / BFS, k = 36: 113 / 108, k = 48: 146 / 120,
+        // k = 64: 208 / 142; up to k = 28 FBS sits on the copy rate and BFS 5-10 % above it).
+        // On signals of 2 GB and more BFS, whose register groups do not overlap, is the
+        // faster one at every k (n = 2^29: 739 / 709 us at k = 16, 744 / 708 at k = 5;
+        // n = 2^28: level).
+        if ((k >= 36 || n >= ((size_t)1 << 29)) && sysconv::has_conv1d_bfs(k))
+            return hip_status(sysconv::launch_conv1d_bfs(d_x, n, h_w, k, d_y, stream));
         return hip_status(sysconv::launch_conv1d_fbs(d_x, n, h_w, k, d_y, stream));
     case SYS_PROJ_FBS: return hip_status(sysconv::launch_conv1d_fbs(d_x, n, h_w, k, d_y, stream));
     case SYS_PROJ_SBM: return hip_status(sysconv::launch_conv1d_sbm(d_x, n, h_w, k, d_y, stream));

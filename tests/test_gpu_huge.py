@@ -58,7 +58,7 @@ def _check_1d(x, y, w, stride, rng, what):
 
 
 @pytest.mark.parametrize("k", [2, 5])
-@pytest.mark.parametrize("proj", ["FBS", "SBM", "BFS", "BSM", "FSM", "FFS"])
+@pytest.mark.parametrize("proj", ["AUTO", "FBS", "SBM", "BFS", "BSM", "FSM", "FFS"])
 def test_1d_paper_shape_stride1(signal, proj, k):
     rng = np.random.default_rng(k)
     w = rng.uniform(-1, 1, k).astype(np.float32)
