@@ -44,6 +44,10 @@
  *     returns; the caller may free or change them immediately.
  *   - Calls are asynchronous: work is enqueued on `stream` (0 = the null
  *     stream) and the call returns without synchronising.
+ *   - A call enqueues kernels and nothing else (no allocation, no memset, no copy, no
+ *     synchronisation), so it may be recorded into a HIP graph by stream capture; a
+ *     replay then uses the taps of the recorded call, which travel in the kernel
+ *     arguments.
  *   - Device buffers need only 4-byte alignment; 16-byte aligned bases and
  *     pitches that are multiples of 4 elements are fastest.
  *   - Arguments are validated before any HIP call is made.  Nothing aborts:
