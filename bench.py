@@ -12,9 +12,10 @@ single JSON line printed at the end carries
 
   value        algorithmic GB/s of that step (4 B per input + 4 B per output + taps,
                divided by wall time between two device synchronisations)
-  roofline     the same bytes over the kernel's own average duration (HIP events
-               recorded around every launch of the timed region, on the launch
-               stream), against the 8 TB/s HBM peak; `traffic` is the HBM byte
+  roofline     the same bytes over the kernel's average duration on the GPU's clock (HIP
+               events on the launch stream at the start and the end of the timed
+               region and at four points in between; elapsed time / launches),
+               against the 8 TB/s HBM peak; `traffic` is the HBM byte
                count of one launch from hardware counters when a calibrated
                reading is stored in profiles/, else null
   cpu_baseline the CPU oracle (plain C, fp64) timed here on the host cores
@@ -113,7 +114,14 @@ def main() -> int:
         return launch, (dxs, dys)
 
     def time_launches(launch, steps, warmup):
-        """(wall seconds for `steps` launches, mean per-launch seconds from HIP events)."""
+        """Time `steps` back-to-back launches.  Returns (wall seconds between two device synchronisations,
+        mean seconds per launch on the GPU's clock, median of the per-batch means).
+
+        HIP events are recorded on the launch stream before the first launch, after the last one and at up to
+        four points in between -- not around every launch: an event pair per launch costs 7 us per step here
+        (n = 2^26, k = 16: 93.6 us per step with pairs, 86.2 us without, 86.5 us in the rocprofv3 kernel
+        trace), which would be charged to the kernel.  A launch's duration is therefore the length of its
+        batch divided by the launches in it; the few gaps between back-to-back kernels are included."""
         # the GPU drops its clocks while the host prepares inputs: keep it busy for ~50 ms
         # first so that the timed launches see steady-state clocks, then the W warm-up steps
         t_spin = time.perf_counter()
@@ -123,17 +131,22 @@ def main() -> int:
             torch.cuda.synchronize()
         for _ in range(warmup):
             launch()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        n_batches = min(5, steps)
+        bounds = [steps * i // n_batches for i in range(n_batches + 1)]
+        evs = [torch.cuda.Event(enable_timing=True) for _ in bounds]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for a, b in evs:
-            a.record(stream)
-            launch()
-            b.record(stream)
+        evs[0].record(stream)
+        for bi in range(n_batches):
+            for _ in range(bounds[bi], bounds[bi + 1]):
+                launch()
+            evs[bi + 1].record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        per = [a.elapsed_time(b) * 1e-3 for a, b in evs]
-        return wall, sum(per) / len(per), sorted(per)[len(per) // 2]
+        total = evs[0].elapsed_time(evs[-1]) * 1e-3
+        per_batch = sorted(evs[bi].elapsed_time(evs[bi + 1]) * 1e-3 / (bounds[bi + 1] - bounds[bi])
+                           for bi in range(n_batches))
+        return wall, total / steps, per_batch[len(per_batch) // 2]
 
     if args.design_space:
         from paper_2010_15884_amd import schedule_model as sm
