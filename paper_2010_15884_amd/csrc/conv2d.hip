@@ -584,6 +584,97 @@ __global__ __launch_bounds__(kBlock) void conv2d_bfs_block_kernel(Taps2D taps, c
         bfs_block_rows<KH, KW, ROWS, true>(taps_f, xrow, yrow, col0, lane, w_img, xp, ow, yp, rows_out);
 }
 
+// ----------------------------------------------------- SBM 2-D, block form ---
+// The SBM array of SbmStrip (PE = c + q, time = p + P*q) in the block form of
+// bfs_block_rows: the ROWS+KH-1 input rows of a block of ROWS output rows are all
+// requested up front and the output rows are then computed one after the other in
+// straight-line code.  Taps arrive transposed (filter column q contiguous).
+template <int KH, int KW, int ROWS, bool EDGE>
+__device__ __forceinline__ void sbm_block_rows(kernarg_floats taps_t, const float* __restrict__ xrow,
+                                               float* __restrict__ yrow, int col, int w_img, long long xp, int ow,
+                                               long long yp, int rows_out, bool lane_valid)
+{
+    constexpr int NIN = ROWS + KH - 1;
+    constexpr bool kReloadTaps = KH * KW > 25;
+    const int rows_in = rows_out + KH - 1;
+
+    float v[NIN][4];
+#pragma unroll
+    for (int rho = 0; rho < NIN; ++rho) {
+        // rows past the end of the block repeat its last row; they only feed output rows
+        // that are not stored
+        const float* p = xrow + (long long)min(rho, rows_in - 1) * xp;
+        if (EDGE) {
+            load4_guarded<false>(p, col, w_img, v[rho]);
+        } else {
+            const f4u t = *reinterpret_cast<const f4u*>(p + col);
+            v[rho][0] = t.x; v[rho][1] = t.y; v[rho][2] = t.z; v[rho][3] = t.w;
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        float z[4];
+#pragma unroll
+        for (int q = 0; q < KW; ++q) {
+            if (q > 0) {                                                   // Z(s) <- Z(s-1)
+                const float below = from_lane_below(z[3]);
+                z[3] = z[2]; z[2] = z[1]; z[1] = z[0]; z[0] = below;
+            }
+            kernarg_floats ft = taps_t + q * KH + (kReloadTaps ? opaque_zero() : 0);
+#pragma unroll
+            for (int p = 0; p < KH; ++p) {
+                const float wv = ft[p];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (p == 0 && q == 0) z[i] = wv * v[r][i];
+                    else z[i] = __builtin_fmaf(wv, v[r + p][i], z[i]);
+                }
+            }
+        }
+        // read the results out KW-1 PEs further down: PE s gets output column s
+#pragma unroll
+        for (int t = 0; t < KW - 1; ++t) {
+            const float above = from_lane_above(z[0]);
+            z[0] = z[1]; z[1] = z[2]; z[2] = z[3]; z[3] = above;
+        }
+        if (r < rows_out && lane_valid) {
+            float* yr = yrow + (long long)r * yp;
+            if (EDGE) {
+                store4_guarded(yr, col, ow, z);
+            } else {
+                f4u t;
+                t.x = z[0]; t.y = z[1]; t.z = z[2]; t.w = z[3];
+                if (SYSCONV_NONTEMPORAL_STORE) __builtin_nontemporal_store(t, reinterpret_cast<f4u*>(yr + col));
+                else *reinterpret_cast<f4u*>(yr + col) = t;
+            }
+        }
+    }
+}
+
+template <int KH, int KW, int ROWS>
+__global__ __launch_bounds__(kBlock) void conv2d_sbm_block_kernel(Taps2D taps_t, const float* __restrict__ x,
+                                                                  float* __restrict__ y, int w_img, long long xp,
+                                                                  int oh, int ow, long long yp, int row_blocks,
+                                                                  int strips, int side, int per_xcd, int valid_lanes)
+{
+    (void)taps_t;
+    kernarg_floats tf = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
+    int rb, strip;
+    if (!wave_tile(per_xcd, row_blocks, strips, side, rb, strip)) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int col0 = strip * kTile * valid_lanes;
+    const int r0 = rb * ROWS;
+    const int rows_out = min(ROWS, oh - r0);
+    const float* xrow = x + (long long)r0 * xp;
+    float* yrow = y + (long long)r0 * yp;
+    const bool lane_valid = lane < valid_lanes;
+    if (col0 + kStrip <= w_img)
+        sbm_block_rows<KH, KW, ROWS, false>(tf, xrow, yrow, col0 + kTile * lane, w_img, xp, ow, yp, rows_out, lane_valid);
+    else
+        sbm_block_rows<KH, KW, ROWS, true>(tf, xrow, yrow, col0 + kTile * lane, w_img, xp, ow, yp, rows_out, lane_valid);
+}
+
 // Lanes of an SBM strip that keep their results: 64 - halo_lanes(kw).  (Rounding the
 // strip width down to whole cache lines was measured and does not pay in 2-D:
 // 4096^2, 5x5: 28.1 us with 63 lanes, 29.0 with 60, 29.3 with 56.)
@@ -697,6 +788,28 @@ hipError_t launch_bfs_block(const float* x, int h, int w, size_t xp, const float
     return hipGetLastError();
 }
 
+template <int KH, int KW, int ROWS>
+hipError_t launch_sbm_block(const float* x, int h, int w, size_t xp, const float* f, float* y, size_t yp,
+                            hipStream_t s)
+{
+    Taps2D taps;
+    float ft[KH * KW];
+    for (int p = 0; p < KH; ++p)
+        for (int q = 0; q < KW; ++q) ft[q * KH + p] = f[p * KW + q];      // filter column q contiguous
+    fill_taps(taps, ft, KH * KW);
+    const int oh = h - KH + 1, ow = w - KW + 1;
+    const int valid_lanes = strip_valid_lanes(KW);
+    const int strips = (ow + kTile * valid_lanes - 1) / (kTile * valid_lanes);
+    const int row_blocks = (oh + ROWS - 1) / ROWS;
+    long long per_xcd;
+    const long long blocks = tile_workgroups(row_blocks, strips, per_xcd);
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((conv2d_sbm_block_kernel<KH, KW, ROWS>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
+                       taps, x, y, w, (long long)xp, oh, ow, (long long)yp, row_blocks, strips, band_width(xp),
+                       (int)per_xcd, valid_lanes);
+    return hipGetLastError();
+}
+
 bool has_conv2d_bfs(int kh, int kw)
 {
     return kh == kw && kh >= 2 && kh <= 11;
@@ -732,12 +845,15 @@ hipError_t launch_conv2d_sbm(const float* x, int h, int w, size_t xp, const floa
 {
     if (kh != kw) return hipErrorInvalidValue;
     switch (kh) {
-    case 2: return launch_strip<2, 2, 2, true>(x, h, w, xp, f, y, yp, s);
-    case 3: return launch_strip<3, 3, 3, true>(x, h, w, xp, f, y, yp, s);
-    case 4: return launch_strip<4, 4, 3, true>(x, h, w, xp, f, y, yp, s);
-    case 5: return launch_strip<5, 5, 3, true>(x, h, w, xp, f, y, yp, s);
-    case 6: return launch_strip<6, 6, 2, true>(x, h, w, xp, f, y, yp, s);
-    case 7: return launch_strip<7, 7, 2, true>(x, h, w, xp, f, y, yp, s);
+    // Up to 7x7 the block form (all loads of a short row block up front) beats the strip walk
+    // (4096^2: 2x2 33.8 -> 30.3 us, 3x3 32.1 -> 28.6, 5x5 34.2 -> 31.4, 7x7 39.2 -> 37.9;
+    // 16384 x 40960, 5x5: 1191 -> 1119 us); block heights from a sweep over 1, 2, 3, 4, 6 rows.
+    case 2: return launch_sbm_block<2, 2, 2>(x, h, w, xp, f, y, yp, s);
+    case 3: return launch_sbm_block<3, 3, 2>(x, h, w, xp, f, y, yp, s);
+    case 4: return launch_sbm_block<4, 4, 2>(x, h, w, xp, f, y, yp, s);
+    case 5: return launch_sbm_block<5, 5, 4>(x, h, w, xp, f, y, yp, s);
+    case 6: return launch_sbm_block<6, 6, 4>(x, h, w, xp, f, y, yp, s);
+    case 7: return launch_sbm_block<7, 7, 4>(x, h, w, xp, f, y, yp, s);
     case 8: return launch_strip<8, 8, 2, true>(x, h, w, xp, f, y, yp, s);
     case 9: return launch_strip<9, 9, 2, true>(x, h, w, xp, f, y, yp, s);
     case 10: return launch_strip<10, 10, 1, true>(x, h, w, xp, f, y, yp, s);
