@@ -1,9 +1,16 @@
 // 2-D valid convolution  y[r][c] = sum_p sum_q x[r+p][c+q] * f[p][q]  (paper
 // Eq. 3; the paper's systolic axis c,q is the image column) as software
 // systolic arrays.  A wavefront always works on a strip of 256 consecutive
-// input columns held four per lane; neighbouring strips overlap by
-// 4*halo_lanes(kw) columns and the PEs whose taps reach past the strip compute
-// values that are never stored.
+// input columns held four per lane.  In the FBS and SBM kernels neighbouring
+// strips overlap by 4*halo_lanes(kw) columns and the PEs whose taps reach past
+// the strip compute values that are never stored; the BFS kernels' strips do
+// not overlap and fetch the kw-1 columns to their right separately.
+//
+//   conv2d_fbs_kernel<RPW>            any kh, kw <= 15: LDS tile, one 1-D FBS pass per filter row
+//   conv2d_bfs_block_kernel<K,K,ROWS> 2x2 .. 7x7: short row block, all loads up front
+//   conv2d_bfs_kernel<K,K,PD>         8x8 .. 11x11: strip walk with rows in flight
+//   conv2d_sbm_block_kernel<K,K,ROWS> 2x2 .. 7x7
+//   conv2d_sbm_kernel<K,K,PD>         8x8 .. 11x11
 #include "launch.h"
 #include "systolic.h"
 
