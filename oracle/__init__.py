@@ -12,8 +12,9 @@ hand-expanded sums, delta filters, linearity, separability, constant / ramp /
 box closed forms, integer-exact data, numpy's and torch's float64 routines as a
 library special case, the paper's recurrence equations (Section 3.1, Table 2,
 Section 5) evaluated literally, and the printed values of Table 4; the strided
-form also against hand sums, every stride-th output of the stride-1 form, numpy's
-correlate subsampled, and the stride-2 recurrences of Table 2.
+forms also against hand sums, every stride-th output of the stride-1 forms, numpy's
+correlate resp. torch's conv2d(stride=2) in float64, delta filters, and (1-D) the
+stride-2 recurrences of Table 2.
 Nothing here is "parity unpinned".
 """
 from __future__ import annotations
@@ -59,6 +60,12 @@ def _load():
             fn = getattr(lib, name)
             fn.argtypes = [fp, ctypes.c_int, ctypes.c_int, ctypes.c_size_t,
                            fp, ctypes.c_int, ctypes.c_int,
+                           dp, ctypes.c_size_t, ctypes.c_int]
+            fn.restype = ctypes.c_int
+        for name in ("oracle_conv2d_strided", "oracle_absdot2d_strided"):
+            fn = getattr(lib, name)
+            fn.argtypes = [fp, ctypes.c_int, ctypes.c_int, ctypes.c_size_t,
+                           fp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                            dp, ctypes.c_size_t, ctypes.c_int]
             fn.restype = ctypes.c_int
         lib.oracle_threads.argtypes = [ctypes.c_int]
@@ -127,6 +134,21 @@ def _run2d(fname, x, f, nthreads):
     return y
 
 
+def _run2d_strided(fname, x, f, stride, nthreads):
+    x = _f32(x, 2)
+    f = _f32(f, 2)
+    h, w_img = x.shape
+    kh, kw = f.shape
+    if kh < 1 or kw < 1 or kh > h or kw > w_img or stride < 1:
+        raise ValueError("filter must fit inside the image and stride must be >= 1")
+    y = np.empty(((h - kh) // stride + 1, (w_img - kw) // stride + 1), dtype=np.float64)
+    rc = getattr(_load(), fname)(_fptr(x), h, w_img, w_img, _fptr(f), kh, kw, int(stride),
+                                 _dptr(y), y.shape[1], int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"{fname} failed with status {rc}")
+    return y
+
+
 def conv1d(x, w, nthreads: int = 1) -> np.ndarray:
     """Eq. 2: y[c] = sum_q x[c+q] * w[q]; fp32 inputs, fp64 result, length n-k+1."""
     return _run1d("oracle_conv1d", x, w, nthreads)
@@ -144,6 +166,15 @@ def absdot1d_strided(x, w, stride: int, nthreads: int = 1) -> np.ndarray:
 def conv2d(x, f, nthreads: int = 1) -> np.ndarray:
     """Eq. 3 on a row-major image: y[r][c] = sum_p sum_q f[p][q] * x[r+p][c+q]."""
     return _run2d("oracle_conv2d", x, f, nthreads)
+
+
+def conv2d_strided(x, f, stride: int, nthreads: int = 1) -> np.ndarray:
+    """y[r][c] = sum_p sum_q f[p][q] * x[stride*r+p][stride*c+q] (the same stride on both axes)."""
+    return _run2d_strided("oracle_conv2d_strided", x, f, stride, nthreads)
+
+
+def absdot2d_strided(x, f, stride: int, nthreads: int = 1) -> np.ndarray:
+    return _run2d_strided("oracle_absdot2d_strided", x, f, stride, nthreads)
 
 
 def absdot1d(x, w, nthreads: int = 1) -> np.ndarray:

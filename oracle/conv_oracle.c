@@ -9,6 +9,8 @@
  *
  * and the strided 1-D form that the stride-2 FBS design of Table 2 (row 3 right)
  * computes:                            Z(c)   = sum_q          x(S*c+q)   * w(q)
+ * and its 2-D analogue (the stride of the paper's Section 6 experiment applied to
+ * both axes):                          Z(c,r) = sum_q sum_p    x(S*c+q,S*r+p) * w(q,p)
  *
  * Readings taken where the paper is silent:
  *   - no filter flip (the equations index x(c+q), so this is cross-correlation);
@@ -129,6 +131,66 @@ int oracle_conv2d(const float *x, int h, int w_img, size_t x_pitch,
                     z += (double)x[(size_t)(r + p) * x_pitch + (size_t)(c + q)]
                        * (double)f[p * kw + q];
             y[(size_t)r * y_pitch + (size_t)c] = z;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * Strided Eq. 3: y[r][c] = sum_p sum_q f[p][q] * x[S*r+p][S*c+q], the same stride on both
+ * axes; (h-kh)/S + 1 rows of (w_img-kw)/S + 1 outputs.  stride 1 is Eq. 3.
+ */
+int oracle_conv2d_strided(const float *x, int h, int w_img, size_t x_pitch,
+                          const float *f, int kh, int kw, int stride,
+                          double *y, size_t y_pitch, int nthreads)
+{
+    if (!x || !f || !y || kh < 1 || kw < 1 || kh > h || kw > w_img || stride < 1) return ORACLE_BAD_ARG;
+    if (x_pitch < (size_t)w_img) return ORACLE_BAD_ARG;
+    const int oh = (h - kh) / stride + 1;
+    const int ow = (w_img - kw) / stride + 1;
+    if (y_pitch < (size_t)ow) return ORACLE_BAD_ARG;
+    const int nt = clamp_threads(nthreads);
+    (void)nt;
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(nt) schedule(static)
+#endif
+    for (int r = 0; r < oh; ++r) {
+        for (int c = 0; c < ow; ++c) {
+            double z = 0.0;
+            for (int p = 0; p < kh; ++p)
+                for (int q = 0; q < kw; ++q)
+                    z += (double)x[(size_t)(stride * r + p) * x_pitch + (size_t)(stride * c + q)]
+                       * (double)f[p * kw + q];
+            y[(size_t)r * y_pitch + (size_t)c] = z;
+        }
+    }
+    return ORACLE_OK;
+}
+
+int oracle_absdot2d_strided(const float *x, int h, int w_img, size_t x_pitch,
+                            const float *f, int kh, int kw, int stride,
+                            double *s, size_t s_pitch, int nthreads)
+{
+    if (!x || !f || !s || kh < 1 || kw < 1 || kh > h || kw > w_img || stride < 1) return ORACLE_BAD_ARG;
+    if (x_pitch < (size_t)w_img) return ORACLE_BAD_ARG;
+    const int oh = (h - kh) / stride + 1;
+    const int ow = (w_img - kw) / stride + 1;
+    if (s_pitch < (size_t)ow) return ORACLE_BAD_ARG;
+    const int nt = clamp_threads(nthreads);
+    (void)nt;
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(nt) schedule(static)
+#endif
+    for (int r = 0; r < oh; ++r) {
+        for (int c = 0; c < ow; ++c) {
+            double z = 0.0;
+            for (int p = 0; p < kh; ++p)
+                for (int q = 0; q < kw; ++q) {
+                    double xv = (double)x[(size_t)(stride * r + p) * x_pitch + (size_t)(stride * c + q)];
+                    double wv = (double)f[p * kw + q];
+                    z += (xv < 0 ? -xv : xv) * (wv < 0 ? -wv : wv);
+                }
+            s[(size_t)r * s_pitch + (size_t)c] = z;
         }
     }
     return ORACLE_OK;

@@ -310,3 +310,43 @@ def test_strided_bad_arguments():
         oracle.conv1d_strided(x, np.zeros(3, np.float32), 0)
     with pytest.raises(ValueError):
         oracle.conv1d_strided(x, np.zeros(9, np.float32), 2)
+
+
+# --------------------------------------------------------------- strided 2-D
+def test_strided_2d_hand_sums():
+    # 5 x 6 image 1..30 row-major, f = [[1, 2], [3, 4]], stride 2: outputs at (r, c) = (0..1, 0..2)
+    x = np.arange(1, 31, dtype=np.float32).reshape(5, 6)
+    f = np.array([[1, 2], [3, 4]], np.float32)
+    # window at (2r, 2c): x[2r][2c]*1 + x[2r][2c+1]*2 + x[2r+1][2c]*3 + x[2r+1][2c+1]*4
+    want = np.array([[1 + 4 + 21 + 32, 3 + 8 + 27 + 40, 5 + 12 + 33 + 48],
+                     [13 + 28 + 57 + 80, 15 + 32 + 63 + 88, 17 + 36 + 69 + 96]], np.float64)
+    assert np.array_equal(oracle.conv2d_strided(x, f, 2), want)
+
+
+@pytest.mark.parametrize("shape,kshape,stride", [((9, 11), (2, 2), 2), ((10, 12), (5, 5), 2), ((11, 13), (5, 5), 2),
+                                                  ((8, 20), (3, 1), 2), ((7, 21), (1, 4), 2), ((15, 15), (15, 15), 2),
+                                                  ((16, 17), (15, 15), 2), ((13, 19), (3, 5), 3)])
+def test_strided_2d_is_the_subsampled_stride1_result(shape, kshape, stride):
+    rng = np.random.default_rng(shape[0] * 100 + kshape[1])
+    x = rng.uniform(0, 1, shape).astype(np.float32)
+    f = rng.uniform(-1, 1, kshape).astype(np.float32)
+    y = oracle.conv2d_strided(x, f, stride)
+    assert y.shape == ((shape[0] - kshape[0]) // stride + 1, (shape[1] - kshape[1]) // stride + 1)
+    assert np.array_equal(y, oracle.conv2d(x, f)[::stride, ::stride])        # same fp64 sums in the same order
+    assert np.array_equal(oracle.absdot2d_strided(x, f, stride), oracle.absdot2d(x, f)[::stride, ::stride])
+    assert np.array_equal(oracle.conv2d_strided(x, f, 1), oracle.conv2d(x, f))
+
+
+def test_strided_2d_against_torch_float64_and_deltas():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(11)
+    x = rng.uniform(0, 1, (23, 31)).astype(np.float32)
+    f = rng.uniform(-1, 1, (4, 6)).astype(np.float32)
+    lib = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64))[None, None],
+                                     torch.from_numpy(f.astype(np.float64))[None, None], stride=2)[0, 0].numpy()
+    assert np.allclose(oracle.conv2d_strided(x, f, 2), lib, rtol=0, atol=1e-13)
+    for p, q in [(0, 0), (3, 0), (0, 5), (2, 3)]:
+        d = np.zeros((4, 6), np.float32)
+        d[p, q] = 1
+        got = oracle.conv2d_strided(x, d, 2)
+        assert np.array_equal(got, x[p:p + 2 * got.shape[0]:2, q:q + 2 * got.shape[1]:2].astype(np.float64))
