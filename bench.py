@@ -196,7 +196,7 @@ def main() -> int:
         return 0
 
     if args.paper_shape:
-        threads, per_thread = 10 * (1 << 20), 16 * 4        # Section 6: "over 10 millions of threads", 16*4 outputs each
+        threads, per_thread = 10 * (1 << 20), 16 * 4        # Section 6: more than ten million threads, 16*4 outputs each
         outputs = threads * per_thread
         paper_1d = {"SBM": (157, 147), "BSM": (67, 49), "FSM": (56, 39), "BFS": (56, 48), "FFS": (33, 30),
                     "FBS": (159, 157)}                      # Table 3, % of the hardware sampler (k = 2, 5)

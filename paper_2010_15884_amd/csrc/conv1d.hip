@@ -193,8 +193,8 @@ __global__ __launch_bounds__(kBlock) void conv1d_sbm_kernel(const float* __restr
     }
 
     // PE s = 4*lane + i of group r now holds output  base + r*per_group + s - (k-1).
-    // Read the result vector out k-1 PEs further down (the `Z.select<CCC>(Q-1)` region
-    // read of the paper's SBM listing): a whole lane at a time while four or more PEs
+    // Read the result vector out k-1 PEs further down (Section 3.1: the results of an
+    // SBM array are taken from PE Q-1 on): a whole lane at a time while four or more PEs
     // remain, then PE by PE.  After that PE s holds output s and the stores line up
     // with the loads.
     int left = k - 1;

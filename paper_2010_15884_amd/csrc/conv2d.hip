@@ -81,8 +81,8 @@ inline long long tile_workgroups(int row_blocks, int strips, long long& per_xcd)
 }
 
 // ------------------------------------------------------------- FBS 2-D -----
-// Section 6.2: "FBS ... converts a 2-D convolution into multiple FBS 1-D
-// convolutions".  A workgroup stages a (4*RPW + kh - 1) x 256 input tile in LDS
+// Section 6.2 describes the 2-D FBS design as a set of 1-D FBS convolutions, one per
+// filter row, that add into the same partial sums.  A workgroup stages a (4*RPW + kh - 1) x 256 input tile in LDS
 // once; each of its four wavefronts then owns RPW output rows (RPW independent
 // partial-sum vectors; RPW = 3, or 2 for tall filters) and, for every filter row p,
 // re-reads the input rows r+p from LDS and runs the 1-D FBS time loop over q on them.
@@ -385,8 +385,8 @@ __global__ __launch_bounds__(kBlock) void conv2d_bfs_kernel(Taps2D taps, const f
 // use, PD in flight); the ring is indexed by row mod (KH+PD) and the row loop is
 // unrolled that many times so that all indices are compile-time constants.
 // Before storing, the result vector is read out KW-1 PEs further down (the
-// paper's `Z.select<CCC>(Q-1)` region read), which lines the stores up with the
-// loads.  Taps arrive transposed (filter column q contiguous).
+// results of an SBM array start at PE Q-1, Section 3.1), which lines the stores up
+// with the loads.  Taps arrive transposed (filter column q contiguous).
 template <int KH, int KW, int PD, bool EDGE>
 struct SbmStrip {
     static constexpr int RS = KH + PD;                                     // ring size
