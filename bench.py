@@ -60,7 +60,8 @@ def _parse():
     ap.add_argument("--paper-shape", action="store_true",
                     help="only time the grid of the paper's Section 6 experiment: 10 Mi 'threads' of 16x4 outputs each "
                          "(671 M outputs), 1-D k in {2, 5} at stride 1 (six designs) and stride 2 (FBS), 2-D 2x2 and "
-                         "5x5 (SBM, FBS, BFS); throughput = outputs / time, as in the paper; prints JSON")
+                         "5x5 at stride 1 (SBM, FBS, BFS) and stride 2 (FBS); throughput = outputs / time, as in the "
+                         "paper; prints JSON")
     return ap.parse_args()
 
 
@@ -201,8 +202,13 @@ def main() -> int:
         paper_1d = {"SBM": (157, 147), "BSM": (67, 49), "FSM": (56, 39), "BFS": (56, 48), "FFS": (33, 30),
                     "FBS": (159, 157)}                      # Table 3, % of the hardware sampler (k = 2, 5)
         paper_2d = {"SBM": (92, 20), "FBS": (114, 24)}      # Table 5 (2x2, 5x5)
-        rng = np.random.default_rng(158846)
         rows = []
+
+        def device_uniform(shape, lo, hi, seed):
+            # inputs of 2.5 - 10 GiB: drawn on the device (seeded), not shipped from the host
+            g = torch.Generator(device="cuda")
+            g.manual_seed(seed)
+            return torch.empty(shape, dtype=torch.float32, device="cuda").uniform_(lo, hi, generator=g)
 
         def timed(launch, read_floats, taps_per_out, row):
             _, k_mean, _ = time_launches(launch, 5, 1)
@@ -212,17 +218,14 @@ def main() -> int:
             rows.append(row)
             print(json.dumps(row), file=sys.stderr, flush=True)
 
-        def rotate(make_x, y_shape):
-            dxs = [make_x() for _ in range(2)]              # 2 x (>= 5 GB) per pass: far past the memory-side cache
-            dys = [torch.empty(y_shape, dtype=torch.float32, device="cuda") for _ in range(2)]
-            return dxs, dys, {"i": 0}
-
-        x1 = torch.from_numpy(W.uniform_f32(rng, -1.0, 1.0, (2 * outputs + 8,)))      # longest 1-D input (stride 2)
+        # two buffer pairs in rotation: >= 5 GB per pass, far past the memory-side cache
         for stride in (1, 2):
             for ki, k in enumerate((2, 5)):
                 taps = W.uniform_f32(np.random.default_rng(15884 + k), -1.0, 1.0, (k,))
                 n = stride * (outputs - 1) + k
-                dxs, dys, st = rotate(lambda: x1[:n].cuda(), (outputs,))
+                dxs = [device_uniform((n,), -1.0, 1.0, 158846 + i) for i in range(2)]
+                dys = [torch.empty((outputs,), dtype=torch.float32, device="cuda") for _ in range(2)]
+                st = {"i": 0}
                 for proj in (("FBS", "SBM", "BFS", "BSM", "FSM", "FFS") if stride == 1 else ("FBS",)):
                     def launch():
                         i = st["i"] = (st["i"] + 1) % 2
@@ -232,22 +235,24 @@ def main() -> int:
                         row["paper_relative_to_FBS"] = round(paper_1d[proj][ki] / paper_1d["FBS"][ki], 3)
                     timed(launch, n, k, row)
                 del dxs, dys
-        del x1
         oh, ow = 16384, outputs // 16384
-        x2 = torch.from_numpy(W.uniform_f32(rng, -1.0, 1.0, (oh + 4, ow + 4)))
-        for ki, kk in enumerate((2, 5)):
-            f = W.uniform_f32(np.random.default_rng(15884 + 10 * kk), -1.0, 1.0, (kk, kk))
-            h, w_img = oh + kk - 1, ow + kk - 1
-            dxs, dys, st = rotate(lambda: x2[:h, :w_img].contiguous().cuda(), (oh, ow))
-            for proj in ("FBS", "SBM", "BFS"):
-                def launch():
-                    i = st["i"] = (st["i"] + 1) % 2
-                    B.sys_conv2d(dxs[i], f, dys[i], projection=proj)
-                row = {"conv": "2-D", "k": f"{kk}x{kk}", "stride": 1, "design": proj}
-                if proj in paper_2d:
-                    row["paper_relative_to_FBS"] = round(paper_2d[proj][ki] / paper_2d["FBS"][ki], 3)
-                timed(launch, h * w_img, kk * kk, row)
-            del dxs, dys
+        for stride in (1, 2):
+            for ki, kk in enumerate((2, 5)):
+                f = W.uniform_f32(np.random.default_rng(15884 + 10 * kk), -1.0, 1.0, (kk, kk))
+                h, w_img = stride * (oh - 1) + kk, stride * (ow - 1) + kk
+                dxs = [device_uniform((h, w_img), 0.0, 1.0, 158856 + i) for i in range(2)]
+                dys = [torch.empty((oh, ow), dtype=torch.float32, device="cuda") for _ in range(2)]
+                st = {"i": 0}
+                for proj in (("FBS", "SBM", "BFS") if stride == 1 else ("FBS",)):
+                    def launch():
+                        i = st["i"] = (st["i"] + 1) % 2
+                        B.sys_conv2d_strided(dxs[i], f, stride, dys[i], projection=proj)
+                    row = {"conv": "2-D", "k": f"{kk}x{kk}", "stride": stride, "design": proj}
+                    if stride == 1 and proj in paper_2d:
+                        row["paper_relative_to_FBS"] = round(paper_2d[proj][ki] / paper_2d["FBS"][ki], 3)
+                    timed(launch, h * w_img, kk * kk, row)
+                del dxs, dys
+                torch.cuda.empty_cache()
         ref = {(r["conv"], r["k"], r["stride"]): r["kernel_us"] for r in rows if r["design"] == "FBS"}
         for r in rows:
             r["relative_to_FBS"] = round(ref[(r["conv"], r["k"], r["stride"])] / r["kernel_us"], 3)

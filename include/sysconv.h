@@ -9,6 +9,9 @@
  *   1-D, Eq. 2 (Section 3.1):  y[c]    = sum_q         x[c+q]      * w[q]
  *   2-D, Eq. 3 (Section 5):    y[r][c] = sum_p sum_q   x[r+p][c+q] * f[p][q]
  *
+ * (also at stride 2, sys_conv1d_strided / sys_conv2d_strided, and for 1-D designs given as
+ * data, sys_conv1d_stt)
+ *
  * No filter flip, no padding: n inputs and k taps give n-k+1 outputs.  The
  * paper's systolic (fast) axis c,q is the column of a row-major image.
  * Data and arithmetic are fp32 (the paper's SIMD8 float vectors, Section 6);
@@ -196,6 +199,27 @@ int sys_conv2d(const float *d_x, int h, int w, size_t x_pitch,
                const float *h_f, int kh, int kw,
                float *d_y, size_t y_pitch,
                int projection, hipStream_t stream);
+
+/*
+ * Strided 2-D valid convolution, the same stride on both axes:
+ *   d_y[r*y_pitch + c] = sum_{p<kh} sum_{q<kw} d_x[(stride*r+p)*x_pitch + stride*c+q] * h_f[p*kw+q]
+ * for r < (h-kh)/stride + 1, c < (w-kw)/stride + 1 (integer divisions).  The paper's
+ * experiment (Section 6) runs its convolutions at stride 1 or 2 and gives the stride-2
+ * design for one axis (Table 2, row 3 right); applying it along the columns and taking
+ * every second row is this library's reading for two axes.
+ *   stride 1  identical to sys_conv2d (every projection).
+ *   stride 2  FBS only (SYS_PROJ_AUTO or SYS_PROJ_FBS); any filter up to SYS_MAX_K2D.
+ *   other strides, or other projections at stride 2: SYS_ERR_UNSUPPORTED
+ *             (sys_conv2d_strided_has reports it); stride < 1: SYS_ERR_SIZE.
+ * Arguments as sys_conv2d; d_y has (h-kh)/stride + 1 rows of (w-kw)/stride + 1 floats.
+ */
+int sys_conv2d_strided(const float *d_x, int h, int w, size_t x_pitch,
+                       const float *h_f, int kh, int kw, int stride,
+                       float *d_y, size_t y_pitch,
+                       int projection, hipStream_t stream);
+
+/* 1 if sys_conv2d_strided(projection) is built for a kh x kw filter at this stride, else 0. */
+int sys_conv2d_strided_has(int projection, int kh, int kw, int stride);
 
 /* 1 if sys_conv1d(projection) is built for a k-tap filter, else 0. */
 int sys_conv1d_has(int projection, int k);

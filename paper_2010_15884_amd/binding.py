@@ -25,7 +25,7 @@ SYS_MAX_K1D = 64
 SYS_MAX_K2D = 15
 
 EXPORTS = ["sys_conv1d", "sys_conv1d_strided", "sys_conv2d", "sys_conv1d_has", "sys_conv1d_strided_has",
-           "sys_conv2d_has", "sys_stt_check", "sys_conv1d_stt", "sys_copy_f32", "sys_status_string",
+           "sys_conv2d_has", "sys_conv2d_strided", "sys_conv2d_strided_has", "sys_stt_check", "sys_conv1d_stt", "sys_copy_f32", "sys_status_string",
            "sys_projection_name", "sys_last_hip_error", "sys_version"]
 
 _lib = None
@@ -92,6 +92,10 @@ def lib() -> ctypes.CDLL:
         L.sys_stt_check.restype = ci
         L.sys_conv1d_stt.argtypes = [vp, sz, fp, ci, vp, ctypes.POINTER(SttDesign), vp]
         L.sys_conv1d_stt.restype = ci
+        L.sys_conv2d_strided.argtypes = [vp, ci, ci, sz, fp, ci, ci, ci, vp, sz, ci, vp]
+        L.sys_conv2d_strided.restype = ci
+        L.sys_conv2d_strided_has.argtypes = [ci, ci, ci, ci]
+        L.sys_conv2d_strided_has.restype = ci
         L.sys_conv1d_has.argtypes = [ci, ci]
         L.sys_conv1d_has.restype = ci
         L.sys_conv2d_has.argtypes = [ci, ci, ci]
@@ -235,6 +239,37 @@ def sys_conv2d(d_x, h_f, d_y=None, projection="AUTO", stream=None):
                             f.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), kh, kw,
                             d_y.data_ptr(), d_y.stride(0), _proj(projection), _stream_handle(stream)))
     return d_y
+
+
+def sys_conv2d_strided(d_x, h_f, stride, d_y=None, projection="AUTO", stream=None):
+    """y[r][c] = sum_p sum_q x[stride*r+p][stride*c+q] f[p][q].  Arguments as sys_conv2d."""
+    import torch
+    _device_f32(d_x, "d_x")
+    if d_x.dim() != 2 or d_x.stride(1) != 1:
+        raise ValueError("d_x must be 2-D with unit column stride")
+    f = _taps(h_f)
+    if f.ndim != 2:
+        raise ValueError("h_f must be 2-D")
+    h, w = d_x.shape
+    kh, kw = f.shape
+    stride = int(stride)
+    ok = stride >= 1 and h >= kh and w >= kw
+    oh, ow = ((h - kh) // stride + 1, (w - kw) // stride + 1) if ok else (0, 0)
+    if d_y is None:
+        d_y = torch.empty((oh, ow), dtype=torch.float32, device=d_x.device)
+    _device_f32(d_y, "d_y")
+    if d_y.dim() != 2 or d_y.stride(1) != 1:
+        raise ValueError("d_y must be 2-D with unit column stride")
+    if d_y.shape[0] < oh or d_y.shape[1] < ow:
+        raise ValueError(f"d_y must have room for {oh} x {ow} outputs")
+    _check(lib().sys_conv2d_strided(d_x.data_ptr(), h, w, d_x.stride(0),
+                                    f.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), kh, kw, stride,
+                                    d_y.data_ptr(), d_y.stride(0), _proj(projection), _stream_handle(stream)))
+    return d_y
+
+
+def sys_conv2d_strided_has(projection, kh: int, kw: int, stride: int) -> bool:
+    return bool(lib().sys_conv2d_strided_has(_proj(projection), int(kh), int(kw), int(stride)))
 
 
 def sys_conv1d_has(projection, k: int) -> bool:

@@ -186,6 +186,31 @@ int sys_conv2d(const float* d_x, int h, int w, size_t x_pitch, const float* h_f,
     }
 }
 
+int sys_conv2d_strided(const float* d_x, int h, int w, size_t x_pitch, const float* h_f, int kh, int kw, int stride,
+                       float* d_y, size_t y_pitch, int projection, hipStream_t stream)
+{
+    if (stride == 1) return sys_conv2d(d_x, h, w, x_pitch, h_f, kh, kw, d_y, y_pitch, projection, stream);
+    if (!d_x || !h_f || !d_y) return SYS_ERR_NULL;
+    if (h < 1 || w < 1 || kh < 1 || kw < 1 || kh > h || kw > w || stride < 1) return SYS_ERR_SIZE;
+    const int oh = (h - kh) / stride + 1, ow = (w - kw) / stride + 1;
+    if (x_pitch < (size_t)w || y_pitch < (size_t)ow) return SYS_ERR_SIZE;
+    if (!known_projection(projection) || kh > SYS_MAX_K2D || kw > SYS_MAX_K2D) return SYS_ERR_UNSUPPORTED;
+    if (!sys_conv2d_strided_has(projection, kh, kw, stride)) return SYS_ERR_UNSUPPORTED;
+    if (misaligned(d_x) || misaligned(d_y)) return SYS_ERR_UNSUPPORTED;
+    if (x_pitch > ((size_t)1 << 31) || y_pitch > ((size_t)1 << 31)) return SYS_ERR_UNSUPPORTED;
+    const size_t x_bytes = ((size_t)(h - 1) * x_pitch + (size_t)w) * sizeof(float);
+    const size_t y_bytes = ((size_t)(oh - 1) * y_pitch + (size_t)ow) * sizeof(float);
+    if (ranges_overlap(d_x, x_bytes, d_y, y_bytes)) return SYS_ERR_ALIAS;
+    return hip_status(sysconv::launch_conv2d_fbs_stride2(d_x, h, w, x_pitch, h_f, kh, kw, d_y, y_pitch, stream));
+}
+
+int sys_conv2d_strided_has(int projection, int kh, int kw, int stride)
+{
+    if (stride == 1) return sys_conv2d_has(projection, kh, kw);
+    if (kh < 1 || kw < 1 || kh > SYS_MAX_K2D || kw > SYS_MAX_K2D || stride != 2) return 0;
+    return (projection == SYS_PROJ_AUTO || projection == SYS_PROJ_FBS) ? 1 : 0;
+}
+
 int sys_copy_f32(const float* d_src, float* d_dst, size_t n, hipStream_t stream)
 {
     if (!d_src || !d_dst) return SYS_ERR_NULL;

@@ -55,6 +55,8 @@ hipError_t launch_conv1d_stt(const float* x, size_t n, const float* w, int k, fl
 
 hipError_t launch_conv2d_fbs(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
                              float* y, size_t yp, hipStream_t s);
+hipError_t launch_conv2d_fbs_stride2(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
+                                     float* y, size_t yp, hipStream_t s);
 bool has_conv2d_bfs(int kh, int kw);
 hipError_t launch_conv2d_bfs(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
                              float* y, size_t yp, hipStream_t s);

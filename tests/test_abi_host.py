@@ -150,3 +150,36 @@ def test_conv1d_strided_has():
             assert B.sys_conv1d_strided_has(proj, k, 1) == B.sys_conv1d_has(proj, k)
         assert not B.sys_conv1d_strided_has("FBS", k, 3) and not B.sys_conv1d_strided_has("FBS", k, 0)
     assert not B.sys_conv1d_strided_has("FBS", 65, 2) and not B.sys_conv1d_strided_has("FBS", 0, 2)
+
+
+@pytest.mark.parametrize("args,want", [
+    ((None, 10, 10, 10, "f", 3, 3, 2, Y, 4, 1), B.SYS_ERR_NULL),
+    ((X, 10, 10, 10, "f", 3, 3, 2, None, 4, 0), B.SYS_ERR_NULL),
+    ((X, 10, 10, 10, "f", 3, 3, 0, Y, 8, 1), B.SYS_ERR_SIZE),
+    ((X, 10, 10, 10, "f", 11, 3, 2, Y, 4, 1), B.SYS_ERR_SIZE),
+    ((X, 10, 10, 9, "f", 3, 3, 2, Y, 4, 1), B.SYS_ERR_SIZE),
+    ((X, 10, 10, 10, "f", 3, 3, 2, Y, 3, 1), B.SYS_ERR_SIZE),            # 4 outputs per row need y_pitch >= 4
+    ((X, 100, 100, 100, "f", 16, 3, 2, Y, 50, 1), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, 100, 100, "f", 3, 3, 3, Y, 50, 1), B.SYS_ERR_UNSUPPORTED),  # only strides 1 and 2 are built
+    ((X, 100, 100, 100, "f", 3, 3, 2, Y, 50, B.SYS_PROJ_SBM), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, 100, 100, "f", 3, 3, 2, Y, 50, B.SYS_PROJ_BFS), B.SYS_ERR_UNSUPPORTED),
+    ((X + 1, 100, 100, 100, "f", 3, 3, 2, Y, 50, 1), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, 100, 100, "f", 3, 3, 2, X + 4 * 5000, 49, 0), B.SYS_ERR_ALIAS),
+    ((X, 100, 100, 100, "f", 3, 3, 1, X + 4 * 5000, 98, 1), B.SYS_ERR_ALIAS),   # stride 1 goes through sys_conv2d
+])
+def test_conv2d_strided_validation(args, want):
+    x, h, w, xp, f, kh, kw, stride, y, yp, proj = args
+    keep = np.ones(256, np.float32)
+    got = B.lib().sys_conv2d_strided(x, h, w, xp, keep.ctypes.data_as(FP) if f else None, kh, kw, stride, y, yp,
+                                     proj, None)
+    assert got == want, B.status_string(got)
+
+
+def test_conv2d_strided_has():
+    for kh, kw in [(1, 1), (2, 2), (5, 5), (3, 8), (15, 15)]:
+        assert B.sys_conv2d_strided_has("AUTO", kh, kw, 2) and B.sys_conv2d_strided_has("FBS", kh, kw, 2)
+        for proj in ("SBM", "BFS", "BSM"):
+            assert not B.sys_conv2d_strided_has(proj, kh, kw, 2)
+            assert B.sys_conv2d_strided_has(proj, kh, kw, 1) == B.sys_conv2d_has(proj, kh, kw)
+        assert not B.sys_conv2d_strided_has("FBS", kh, kw, 3) and not B.sys_conv2d_strided_has("FBS", kh, kw, 0)
+    assert not B.sys_conv2d_strided_has("FBS", 16, 3, 2)

@@ -105,3 +105,31 @@ def test_2d_paper_shape(image, proj, kk):
     scale = np.abs(win) @ np.abs(f64)
     bad = np.abs(got - ref) > TOL * scale
     assert not bad.any(), f"{proj} {kk}x{kk}: {int(bad.sum())} sampled outputs off, first at {rows[bad.argmax()]},{cols[bad.argmax()]}"
+
+
+@pytest.mark.parametrize("kk", [2, 5])
+def test_2d_paper_shape_stride2(kk):
+    rng = np.random.default_rng(60 + kk)
+    f = rng.uniform(-1, 1, (kk, kk)).astype(np.float32)
+    oh, ow = 16384, OUTPUTS // 16384
+    x = _uniform((2 * (oh - 1) + kk, 2 * (ow - 1) + kk), 158849)          # 10.7 GB: offsets beyond 2^33 bytes
+    y = B.sys_conv2d_strided(x, f, 2, projection="FBS")
+    torch.cuda.synchronize()
+    assert y.shape == (oh, ow)
+    rows = np.concatenate([np.arange(0, 12), np.arange(oh - 12, oh), rng.integers(0, oh, 3000),
+                           np.full(200, 6553), np.full(200, 13107)])       # rows around 2^32 and 2^33 bytes of input
+    cols = np.concatenate([rng.integers(0, ow, len(rows) - 400), np.arange(0, 100), np.arange(ow - 100, ow),
+                           rng.integers(0, ow, 200)])
+    r = torch.from_numpy(rows).cuda()
+    c = torch.from_numpy(cols).cuda()
+    ar = torch.arange(kk, device="cuda")
+    win = x[(2 * r[:, None, None] + ar[None, :, None]), (2 * c[:, None, None] + ar[None, None, :])]
+    win = win.cpu().numpy().astype(np.float64).reshape(len(rows), kk * kk)
+    got = y[r, c].cpu().numpy().astype(np.float64)
+    f64 = f.astype(np.float64).reshape(-1)
+    ref = win @ f64
+    scale = np.abs(win) @ np.abs(f64)
+    bad = np.abs(got - ref) > TOL * scale
+    assert not bad.any(), f"{kk}x{kk}: {int(bad.sum())} sampled outputs off, first at {rows[bad.argmax()]},{cols[bad.argmax()]}"
+    del x, y
+    torch.cuda.empty_cache()
