@@ -9,8 +9,12 @@ five), and ``model`` evaluates the paper's Section 6.2 model:
     utilisation = outputs * taps / (#lanes * #time steps)
 
 where #lanes is the length of the *virtual* PE vector (the extent of P.z) and
-#time steps the extent of s^T.z.  With 16 outputs and 5 taps this reproduces
-the paper's Table 4.
+#time steps the extent of s^T.z, and the table's register count: every variable
+keeps one value per PE, a passed variable s^T.e more (the history of Section
+4.1's general code), over 16 PEs for the designs that give each output its own
+PE (SBM counted with its 16 outputs, not its 20 vector lanes) and over Q PEs
+for those whose PE is the tap.  With 16 outputs and 5 taps this reproduces all
+eighteen numbers of the paper's Table 4.
 
 ``wave64`` evaluates the same two figures for the way the HIP kernels lay each
 design over a 64-lane wavefront.
@@ -86,11 +90,15 @@ def model(design: str, n_out: int = 16, n_taps: int = 5) -> Dict[str, float]:
     t = TRANSFORMS[design]
     lanes = extent(t.alloc, n_out, n_taps)
     steps = extent(t.sched, n_out, n_taps)
+    deps = DEPENDENCES[design]
+    depth = sum((t.sched[0] * deps[v][0] + t.sched[1] * deps[v][1] + 1) if v in deps else 1 for v in "XWZ")
+    pes = n_out if t.alloc[0] != 0 else n_taps
     return {
         "lanes": lanes,
         "steps": steps,
         "outturn": n_out / steps,
         "utilisation": n_out * n_taps / (lanes * steps),
+        "registers": pes * depth,
     }
 
 

@@ -108,11 +108,12 @@ def test_table4_printed_values():
         for line in fh:
             if line.startswith("#") or not line.strip():
                 continue
-            name, outturn, util = line.split()
-            rows[name] = (float(outturn), float(util))
+            name, outturn, util, regs = line.split()
+            rows[name] = (float(outturn), float(util), int(regs))
     assert set(rows) == set(DESIGNS)
-    for name, (outturn, util) in rows.items():
+    for name, (outturn, util, regs) in rows.items():
         m = sm.model(name, 16, 5)
+        assert m["registers"] == regs, name
         # the paper prints two significant digits
         assert abs(m["outturn"] - outturn) < 0.005 + 1e-12, name
         assert abs(100 * m["utilisation"] - util) < 0.5, name
