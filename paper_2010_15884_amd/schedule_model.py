@@ -86,13 +86,14 @@ def movement(design: str) -> Dict[str, Tuple[int, int]]:
             for v, e in DEPENDENCES[design].items()}
 
 
-def model(design: str, n_out: int = 16, n_taps: int = 5) -> Dict[str, float]:
-    t = TRANSFORMS[design]
-    lanes = extent(t.alloc, n_out, n_taps)
-    steps = extent(t.sched, n_out, n_taps)
-    deps = DEPENDENCES[design]
-    depth = sum((t.sched[0] * deps[v][0] + t.sched[1] * deps[v][1] + 1) if v in deps else 1 for v in "XWZ")
-    pes = n_out if t.alloc[0] != 0 else n_taps
+def model_of(transform: Transform, deps: Dict[str, Tuple[int, int]], n_out: int = 16, n_taps: int = 5) -> Dict[str, float]:
+    """Section 6.2's figures for any design given as a transform and the dependence
+    vectors of its passed variables (a subset of X, W, Z)."""
+    lanes = extent(transform.alloc, n_out, n_taps)
+    steps = extent(transform.sched, n_out, n_taps)
+    depth = sum((transform.sched[0] * deps[v][0] + transform.sched[1] * deps[v][1] + 1) if v in deps else 1
+                for v in "XWZ")
+    pes = n_out if transform.alloc[0] != 0 else n_taps
     return {
         "lanes": lanes,
         "steps": steps,
@@ -100,6 +101,11 @@ def model(design: str, n_out: int = 16, n_taps: int = 5) -> Dict[str, float]:
         "utilisation": n_out * n_taps / (lanes * steps),
         "registers": pes * depth,
     }
+
+
+def model(design: str, n_out: int = 16, n_taps: int = 5) -> Dict[str, float]:
+    """The same for one of the paper's six designs."""
+    return model_of(TRANSFORMS[design], DEPENDENCES[design], n_out, n_taps)
 
 
 def wave64(design: str, n_taps: int, groups: int = 4, tile: int = 4, lanes: int = 64) -> Dict[str, float]:

@@ -141,3 +141,14 @@ def test_wave64_model():
     # FFS with 16-PE arrays has exactly the paper's Table 4 utilisation at K = 5: 16*5/(16*35)
     assert sm.wave64("FFS", 5)["utilisation"] == pytest.approx(sm.model("FFS", 16, 5)["utilisation"])
     assert sm.wave64("BFS", 5)["utilisation"] == pytest.approx(5 / 8)
+
+
+def test_model_of_unlisted_designs():
+    # SBM whose sums move every second step: PE = c + q, time = c + 2q -> 20 lanes, 24 steps for 16 outputs, 5 taps
+    m = sm.model_of(sm.Transform((1, 1), (1, 2)), {"X": (-1, 1), "Z": (0, 1)}, 16, 5)
+    assert (m["lanes"], m["steps"]) == (20, 24)
+    assert m["utilisation"] == pytest.approx(80 / (20 * 24))
+    assert m["registers"] == 16 * (2 + 1 + 3)                    # X waits one step, W is loaded, Z two steps
+    # everything loaded, sums stay, skewed start: the BFS schedule without weight forwarding
+    m = sm.model_of(sm.Transform((1, 0), (1, 1)), {"Z": (0, 1)}, 16, 5)
+    assert (m["lanes"], m["steps"], m["registers"]) == (16, 20, 16 * 4)
