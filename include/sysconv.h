@@ -104,7 +104,8 @@ typedef enum {
  *   h_w   host, k floats, 1 <= k <= min(n, SYS_MAX_K1D)
  *   d_y   device, n-k+1 floats (written; nothing else is touched)
  *   projection  a sys_projection_t; every projection accepts every k in range
- *         (sys_conv1d_has reports it)
+ *         (sys_conv1d_has reports it).  SYS_PROJ_AUTO is FBS, and BFS from 36 taps on
+ *         or for n >= 2^29, where BFS measures faster on MI355X.
  */
 int sys_conv1d(const float *d_x, size_t n,
                const float *h_w, int k,
@@ -191,7 +192,8 @@ int sys_conv1d_stt(const float *d_x, size_t n,
  *   h_f      host, kh*kw floats row-major, 1 <= kh <= min(h, SYS_MAX_K2D), same for kw / w
  *   d_y      device, h-kh+1 rows of w-kw+1 floats, row stride y_pitch elements
  *            (>= w-kw+1); elements between rows are left untouched
- *   projection  AUTO and FBS accept every filter in range; BFS and SBM are built
+ *   projection  AUTO and FBS accept every filter in range (AUTO: BFS for square filters
+ *            up to 7x7, SBM for 8x8 .. 11x11, FBS otherwise); BFS and SBM are built
  *            for a fixed list of filter sizes (sys_conv2d_has) and return
  *            SYS_ERR_UNSUPPORTED otherwise; BSM, FSM and FFS are 1-D only.
  */
