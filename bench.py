@@ -18,6 +18,8 @@ single JSON line printed at the end carries
                against the 8 TB/s HBM peak; `traffic` is the HBM byte
                count of one launch from hardware counters when a calibrated
                reading is stored in profiles/, else null
+  roofline_alu the same for the 8192^2, 11x11 workload, which is bound by the vector ALUs:
+               2 x multiply-adds / kernel time against the 78.6 TFLOP/s fp32 vector peak
   cpu_baseline the CPU oracle (plain C, fp64) timed here on the host cores
   also         all five workloads and every projection built for them, each with
                GB/s, Gtap/s and its fraction of the HBM and fp32-FMA peaks, a plain
@@ -366,6 +368,19 @@ def main() -> int:
                 also.append(row)
                 del ln, kp
         result["also"] = also
+        # the one workload that is bound by the vector ALUs, not by HBM: its own roofline object
+        # (121 multiply-adds per 8 bytes; peak = 256 CUs x 64 lanes x 2.4 GHz x 2 flop = 78.6 TFLOP/s fp32)
+        alu = [r for r in also if r["workload"] == "conv2d_8k_11x11"]
+        if alu:
+            best = max(alu, key=lambda r: r["Gtap/s"])
+            kern = {"SBM": "conv2d_sbm_kernel<11, 11, 1>", "BFS": "conv2d_bfs_kernel<11, 11, 1>",
+                    "FBS": "conv2d_fbs_kernel<2>"}[best["projection"]]
+            result["roofline_alu"] = {
+                "workload": "conv2d_8k_11x11", "projection": best["projection"], "kernel": kern, "bound": "alu",
+                "achieved": round(2 * best["Gtap/s"] / 1e3, 2), "peak": round(2 * FMA_PEAK_G / 1e3, 1),
+                "unit": "TFLOP/s", "frac": round(best["Gtap/s"] / FMA_PEAK_G, 4),
+                "traffic": _stored_traffic(f"conv2d_{best['projection'].lower()}_11x11_8k"),
+                "kernel_us_mean": best["kernel_us_mean"]}
 
     # ---------------------------------------------------------- CPU baseline
     if not args.no_cpu:
