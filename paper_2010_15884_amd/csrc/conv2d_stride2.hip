@@ -121,6 +121,127 @@ __global__ __launch_bounds__(kBlock) void conv2d_fbs_stride2_kernel(TapsStride2D
     }
 }
 
+// ------------------------------------------------------------ block form ----
+// For the small square filters of the paper's experiment (Section 6) the same array
+// without LDS: a wavefront takes ROWS output rows of a strip of 512 input columns,
+// requests all 2*(ROWS-1)+KH input rows up front (eight consecutive inputs per lane and
+// row) and then, input row by input row, builds the shifted windows of the even and of
+// the odd chain once and applies them to every output row whose filter covers that input
+// row (p = rho - 2r).  Strips overlap like the tiles above: the PEs whose even chain
+// would reach past lane 63 compute values that are never stored.
+template <int KH, int KW, int ROWS, bool EDGE>
+__device__ __forceinline__ void stride2_block_rows(kernarg_floats taps_f, const float* __restrict__ xrow,
+                                                   float* __restrict__ yrow, int in_col, int out_col, int w_img,
+                                                   long long xp, int ow, long long yp, int rows_out, bool lane_valid)
+{
+    constexpr int NIN = 2 * (ROWS - 1) + KH;
+    constexpr int KE = (KW + 1) / 2, KO = KW / 2;
+    const int rows_in = 2 * (rows_out - 1) + KH;
+
+    float v[NIN][8];
+#pragma unroll
+    for (int rho = 0; rho < NIN; ++rho) {
+        // rows past the end of the block repeat its last row; they only feed output rows
+        // that are not stored
+        const float* p = xrow + (long long)min(rho, rows_in - 1) * xp;
+        if (EDGE) {
+            float lo[4], hi[4];
+            load4_guarded<false>(p, in_col, w_img, lo);
+            load4_guarded<false>(p, in_col + 4, w_img, hi);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { v[rho][i] = lo[i]; v[rho][4 + i] = hi[i]; }
+        } else {
+            const f4u lo = *reinterpret_cast<const f4u*>(p + in_col), hi = *reinterpret_cast<const f4u*>(p + in_col + 4);
+            v[rho][0] = lo.x; v[rho][1] = lo.y; v[rho][2] = lo.z; v[rho][3] = lo.w;
+            v[rho][4] = hi.x; v[rho][5] = hi.y; v[rho][6] = hi.z; v[rho][7] = hi.w;
+        }
+    }
+
+    float acc[ROWS][4];
+#pragma unroll
+    for (int rho = 0; rho < NIN; ++rho) {
+        float ev[KE + 3], od[KO + 3];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { ev[i] = v[rho][2 * i]; od[i] = v[rho][2 * i + 1]; }
+#pragma unroll
+        for (int m = 4; m < KE + 3; ++m) ev[m] = from_lane_above(ev[m - 4]);
+#pragma unroll
+        for (int m = 4; m < KO + 3; ++m) od[m] = from_lane_above(od[m - 4]);
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            const int p = rho - 2 * r;                                     // compile-time
+            if (p < 0 || p >= KH) continue;
+#pragma unroll
+            for (int q = 0; q < KW; ++q) {
+                const float wv = taps_f[p * KW + q];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float xv = (q & 1) ? od[q / 2 + i] : ev[q / 2 + i];
+                    if (p == 0 && q == 0) acc[r][i] = wv * xv;
+                    else acc[r][i] = __builtin_fmaf(wv, xv, acc[r][i]);
+                }
+            }
+            if (p == KH - 1 && r < rows_out && lane_valid) {
+                float* yr = yrow + (long long)r * yp;
+                if (EDGE) {
+                    store4_guarded(yr, out_col, ow, acc[r]);
+                } else {
+                    f4u t;
+                    t.x = acc[r][0]; t.y = acc[r][1]; t.z = acc[r][2]; t.w = acc[r][3];
+                    if (SYSCONV_NONTEMPORAL_STORE) __builtin_nontemporal_store(t, reinterpret_cast<f4u*>(yr + out_col));
+                    else *reinterpret_cast<f4u*>(yr + out_col) = t;
+                }
+            }
+        }
+    }
+}
+
+// The taps (row-major, as the caller gave them) are the first kernel argument.
+template <int KH, int KW, int ROWS>
+__global__ __launch_bounds__(kBlock) void conv2d_fbs_stride2_block_kernel(Taps2D taps, const float* __restrict__ x,
+                                                                          float* __restrict__ y, int w_img,
+                                                                          long long xp, int oh, int ow, long long yp,
+                                                                          int row_blocks, int strips, int side,
+                                                                          int per_xcd)
+{
+    (void)taps;
+    kernarg_floats tf = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
+    int rb, strip;
+    if (!wave_tile(per_xcd, row_blocks, strips, side, rb, strip)) return;
+    constexpr int valid_lanes = kWave - halo_lanes((KW + 1) / 2);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int out_col0 = strip * kTile * valid_lanes;
+    const int r0 = rb * ROWS;
+    const int rows_out = min(ROWS, oh - r0);
+    const float* xrow = x + (long long)(2 * r0) * xp;
+    float* yrow = y + (long long)r0 * yp;
+    const bool lane_valid = lane < valid_lanes;
+    const int in_col = 2 * out_col0 + 2 * kTile * lane, out_col = out_col0 + kTile * lane;
+    // interior strips: all 512 input columns exist, and then so do the valid lanes' outputs
+    if (2 * out_col0 + kCols <= w_img)
+        stride2_block_rows<KH, KW, ROWS, false>(tf, xrow, yrow, in_col, out_col, w_img, xp, ow, yp, rows_out, lane_valid);
+    else
+        stride2_block_rows<KH, KW, ROWS, true>(tf, xrow, yrow, in_col, out_col, w_img, xp, ow, yp, rows_out, lane_valid);
+}
+
+template <int KH, int KW, int ROWS>
+hipError_t launch_block(const float* x, int h, int w, size_t xp, const float* f, float* y, size_t yp, hipStream_t s)
+{
+    Taps2D taps;
+    for (int i = 0; i < kTaps2DLen; ++i) taps.f[i] = i < KH * KW ? f[i] : 0.0f;
+    const int oh = (h - KH) / 2 + 1, ow = (w - KW) / 2 + 1;
+    const int cols = kTile * (kWave - halo_lanes((KW + 1) / 2));
+    const int strips = (ow + cols - 1) / cols;
+    const int row_blocks = (oh + ROWS - 1) / ROWS;
+    long long per_xcd;
+    const long long blocks = tile_workgroups(row_blocks, strips, per_xcd);
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((conv2d_fbs_stride2_block_kernel<KH, KW, ROWS>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
+                       taps, x, y, w, (long long)xp, oh, ow, (long long)yp, row_blocks, strips, band_width(xp),
+                       (int)per_xcd);
+    return hipGetLastError();
+}
+
 template <int RPW>
 hipError_t launch_tiles(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw, float* y, size_t yp,
                         hipStream_t s)
@@ -150,6 +271,18 @@ hipError_t launch_tiles(const float* x, int h, int w, size_t xp, const float* f,
 hipError_t launch_conv2d_fbs_stride2(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
                                      float* y, size_t yp, hipStream_t s)
 {
+    // Square filters up to 5x5 run the block form, two output rows per wavefront (8192^2, 5x5: 70 us
+    // against 88 us for the LDS tiles and 56 us for a copy of the same bytes; 1, 3 and 4 rows: 83, 68, 74 us;
+    // 2x2: 58.6 against 64.8 us); everything else the tiles.
+    if (kh == kw) {
+        switch (kh) {
+        case 2: return launch_block<2, 2, 2>(x, h, w, xp, f, y, yp, s);
+        case 3: return launch_block<3, 3, 2>(x, h, w, xp, f, y, yp, s);
+        case 4: return launch_block<4, 4, 2>(x, h, w, xp, f, y, yp, s);
+        case 5: return launch_block<5, 5, 2>(x, h, w, xp, f, y, yp, s);
+        default: break;
+        }
+    }
     return launch_tiles<2>(x, h, w, xp, f, kh, kw, y, yp, s);
 }
 
