@@ -141,10 +141,14 @@ def _taps(w) -> np.ndarray:
 
 
 def _stream_handle(stream) -> Optional[int]:
-    if stream is None:
-        import torch
-        return torch.cuda.current_stream().cuda_stream
-    return int(stream)
+    """The hipStream_t to launch on: the caller's, else torch's current stream."""
+    if stream is not None:
+        return int(stream)
+    import torch
+    raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)      # the short way, when this torch has it
+    if raw is not None:
+        return raw(torch.cuda.current_device())
+    return torch.cuda.current_stream().cuda_stream
 
 
 def _device_f32(t, what):
