@@ -14,7 +14,10 @@ library special case, the paper's recurrence equations (Section 3.1, Table 2,
 Section 5) evaluated literally, and the printed values of Table 4; the strided
 forms also against hand sums, every stride-th output of the stride-1 forms, numpy's
 correlate resp. torch's conv2d(stride=2) in float64, delta filters, and (1-D) the
-stride-2 recurrences of Table 2.
+stride-2 recurrences of Table 2.  The scale routines (``absdot*``) are pinned by hand-expanded
+sums with distinct magnitudes (``tests/golden/hand_sums.txt``) and, bit for bit, by the pinned
+convolutions applied to the magnitudes; the pitch arguments of the C routines by padded buffers
+whose padding holds NaN resp. a sentinel.
 Nothing here is "parity unpinned".
 """
 from __future__ import annotations
@@ -119,34 +122,72 @@ def _run1d_strided(fname, x, w, stride, nthreads):
     return y
 
 
-def _run2d(fname, x, f, nthreads):
+_SENTINEL = -12345.678        # what the gaps between result rows hold before the call
+
+
+def _padded_input(x, x_pitch):
+    """The image laid out with a row stride of x_pitch elements; the padding holds NaN so that a
+    read outside the image shows up in the result."""
+    h, w_img = x.shape
+    if x_pitch is None or x_pitch == w_img:
+        return x, w_img
+    if x_pitch < w_img:
+        raise ValueError("x_pitch must be >= the image width")
+    buf = np.full((h, x_pitch), np.nan, dtype=np.float32)
+    buf[:, :w_img] = x
+    return buf, x_pitch
+
+
+def _pitched_output(shape, y_pitch):
+    """Result buffer with a row stride of y_pitch elements, padding pre-set to a sentinel that a
+    correct oracle leaves alone."""
+    oh, ow = shape
+    if y_pitch is None or y_pitch == ow:
+        return np.empty((oh, ow), dtype=np.float64), ow
+    if y_pitch < ow:
+        raise ValueError("y_pitch must be >= the output width")
+    return np.full((oh, y_pitch), _SENTINEL, dtype=np.float64), y_pitch
+
+
+def _unpad_output(buf, shape):
+    oh, ow = shape
+    if buf.shape[1] != ow and not np.all(buf[:, ow:] == _SENTINEL):
+        raise RuntimeError("the oracle wrote between the rows of its result")
+    return np.ascontiguousarray(buf[:, :ow])
+
+
+
+def _run2d(fname, x, f, nthreads, x_pitch=None, y_pitch=None):
     x = _f32(x, 2)
     f = _f32(f, 2)
     h, w_img = x.shape
     kh, kw = f.shape
     if kh < 1 or kw < 1 or kh > h or kw > w_img:
         raise ValueError("filter must fit inside the image")
-    y = np.empty((h - kh + 1, w_img - kw + 1), dtype=np.float64)
-    rc = getattr(_load(), fname)(_fptr(x), h, w_img, w_img, _fptr(f), kh, kw,
-                                 _dptr(y), y.shape[1], int(nthreads))
+    shape = (h - kh + 1, w_img - kw + 1)
+    xin, xp = _padded_input(x, x_pitch)
+    y, yp = _pitched_output(shape, y_pitch)
+    rc = getattr(_load(), fname)(_fptr(xin), h, w_img, xp, _fptr(f), kh, kw, _dptr(y), yp, int(nthreads))
     if rc != 0:
         raise RuntimeError(f"{fname} failed with status {rc}")
-    return y
+    return _unpad_output(y, shape)
 
 
-def _run2d_strided(fname, x, f, stride, nthreads):
+def _run2d_strided(fname, x, f, stride, nthreads, x_pitch=None, y_pitch=None):
     x = _f32(x, 2)
     f = _f32(f, 2)
     h, w_img = x.shape
     kh, kw = f.shape
     if kh < 1 or kw < 1 or kh > h or kw > w_img or stride < 1:
         raise ValueError("filter must fit inside the image and stride must be >= 1")
-    y = np.empty(((h - kh) // stride + 1, (w_img - kw) // stride + 1), dtype=np.float64)
-    rc = getattr(_load(), fname)(_fptr(x), h, w_img, w_img, _fptr(f), kh, kw, int(stride),
-                                 _dptr(y), y.shape[1], int(nthreads))
+    shape = ((h - kh) // stride + 1, (w_img - kw) // stride + 1)
+    xin, xp = _padded_input(x, x_pitch)
+    y, yp = _pitched_output(shape, y_pitch)
+    rc = getattr(_load(), fname)(_fptr(xin), h, w_img, xp, _fptr(f), kh, kw, int(stride), _dptr(y), yp,
+                                 int(nthreads))
     if rc != 0:
         raise RuntimeError(f"{fname} failed with status {rc}")
-    return y
+    return _unpad_output(y, shape)
 
 
 def conv1d(x, w, nthreads: int = 1) -> np.ndarray:
@@ -163,18 +204,21 @@ def absdot1d_strided(x, w, stride: int, nthreads: int = 1) -> np.ndarray:
     return _run1d_strided("oracle_absdot1d_strided", x, w, stride, nthreads)
 
 
-def conv2d(x, f, nthreads: int = 1) -> np.ndarray:
-    """Eq. 3 on a row-major image: y[r][c] = sum_p sum_q f[p][q] * x[r+p][c+q]."""
-    return _run2d("oracle_conv2d", x, f, nthreads)
+def conv2d(x, f, nthreads: int = 1, x_pitch=None, y_pitch=None) -> np.ndarray:
+    """Eq. 3 on a row-major image: y[r][c] = sum_p sum_q f[p][q] * x[r+p][c+q].
+
+    x_pitch / y_pitch (elements) make the C routine work on buffers whose rows are further apart
+    than the image resp. the result is wide; the returned array is always the compact result."""
+    return _run2d("oracle_conv2d", x, f, nthreads, x_pitch, y_pitch)
 
 
-def conv2d_strided(x, f, stride: int, nthreads: int = 1) -> np.ndarray:
+def conv2d_strided(x, f, stride: int, nthreads: int = 1, x_pitch=None, y_pitch=None) -> np.ndarray:
     """y[r][c] = sum_p sum_q f[p][q] * x[stride*r+p][stride*c+q] (the same stride on both axes)."""
-    return _run2d_strided("oracle_conv2d_strided", x, f, stride, nthreads)
+    return _run2d_strided("oracle_conv2d_strided", x, f, stride, nthreads, x_pitch, y_pitch)
 
 
-def absdot2d_strided(x, f, stride: int, nthreads: int = 1) -> np.ndarray:
-    return _run2d_strided("oracle_absdot2d_strided", x, f, stride, nthreads)
+def absdot2d_strided(x, f, stride: int, nthreads: int = 1, x_pitch=None, y_pitch=None) -> np.ndarray:
+    return _run2d_strided("oracle_absdot2d_strided", x, f, stride, nthreads, x_pitch, y_pitch)
 
 
 def absdot1d(x, w, nthreads: int = 1) -> np.ndarray:
@@ -182,8 +226,9 @@ def absdot1d(x, w, nthreads: int = 1) -> np.ndarray:
     return _run1d("oracle_absdot1d", x, w, nthreads)
 
 
-def absdot2d(x, f, nthreads: int = 1) -> np.ndarray:
-    return _run2d("oracle_absdot2d", x, f, nthreads)
+def absdot2d(x, f, nthreads: int = 1, x_pitch=None, y_pitch=None) -> np.ndarray:
+    """sum_p sum_q |x[r+p][c+q]| |f[p][q]| -- the scale of the 2-D parity metric."""
+    return _run2d("oracle_absdot2d", x, f, nthreads, x_pitch, y_pitch)
 
 
 def max_rel_err(y_test, y_ref, scale) -> float:

@@ -26,18 +26,30 @@ def _hand_cases():
             line = line.strip()
             if not line or line.startswith("#"):
                 continue
-            kind, x, w, y = [p.strip() for p in line.split("|")]
-            if kind == "1d":
-                cases.append((kind, _parse_rows(x)[0], _parse_rows(w)[0], _parse_rows(y)[0].astype(np.float64)))
+            parts = [p.strip() for p in line.split("|")]
+            kind, x, w, y = parts[:4]
+            stride = int(parts[4]) if len(parts) > 4 else 1
+            if kind in ("1d", "abs1d"):
+                cases.append((kind, _parse_rows(x)[0], _parse_rows(w)[0], _parse_rows(y)[0].astype(np.float64), stride))
             else:
-                cases.append((kind, _parse_rows(x), _parse_rows(w), _parse_rows(y).astype(np.float64)))
+                cases.append((kind, _parse_rows(x), _parse_rows(w), _parse_rows(y).astype(np.float64), stride))
     return cases
 
 
-@pytest.mark.parametrize("case", _hand_cases(), ids=lambda c: f"{c[0]}-{c[1].shape}-{c[2].shape}")
+def _hand_eval(kind, x, w, stride, ora=oracle):
+    if kind == "1d":
+        return ora.conv1d(x, w)
+    if kind == "2d":
+        return ora.conv2d(x, w)
+    if kind == "abs1d":
+        return ora.absdot1d(x, w) if stride == 1 else ora.absdot1d_strided(x, w, stride)
+    return ora.absdot2d(x, w) if stride == 1 else ora.absdot2d_strided(x, w, stride)
+
+
+@pytest.mark.parametrize("case", _hand_cases(), ids=lambda c: f"{c[0]}-{c[1].shape}-{c[2].shape}-s{c[4]}")
 def test_hand_expanded_sums(case):
-    kind, x, w, y = case
-    got = oracle.conv1d(x, w) if kind == "1d" else oracle.conv2d(x, w)
+    kind, x, w, y, stride = case
+    got = _hand_eval(kind, x, w, stride)
     assert got.shape == y.shape
     assert np.array_equal(got, y)
 
@@ -243,6 +255,88 @@ def test_absdot_and_metric():
     # a non-zero output where every product is zero can never be right
     assert oracle.max_rel_err(ref + np.array([0.0, 0.0, 1e-30]), ref, scale) == float("inf")
     assert oracle.max_rel_err(np.array([np.nan, 2.0, 0.0]), ref, scale) == float("inf")
+
+
+# ------------------------------------------- the scale of the metric, sum |x||f|
+# The scale is the definition applied to the magnitudes: same windows, same order of the fp64 sums.
+# So it must equal conv(|x|, |f|) bit for bit -- with conv pinned above, any indexing mistake in the
+# scale routines (transposed window, swapped p and q, pitch taken for width, stride on one axis only) shows.
+@pytest.mark.parametrize("n,k,stride", [(300, 5, 1), (257, 16, 1), (64, 64, 1), (301, 7, 2), (302, 6, 3)])
+def test_absdot1d_is_the_definition_on_magnitudes(n, k, stride):
+    rng = np.random.default_rng(500 + n + k)
+    x = rng.uniform(-1, 1, n).astype(np.float32)
+    w = rng.uniform(-1, 1, k).astype(np.float32)
+    if stride == 1:
+        assert np.array_equal(oracle.absdot1d(x, w), oracle.conv1d(np.abs(x), np.abs(w)))
+    assert np.array_equal(oracle.absdot1d_strided(x, w, stride), oracle.conv1d_strided(np.abs(x), np.abs(w), stride))
+
+
+@pytest.mark.parametrize("shape,kshape,stride", [((23, 41), (2, 3), 1), ((40, 19), (5, 2), 1), ((31, 37), (11, 11), 1),
+                                                  ((17, 50), (1, 7), 1), ((50, 17), (7, 1), 1), ((26, 45), (3, 5), 2),
+                                                  ((45, 26), (4, 2), 3)])
+def test_absdot2d_is_the_definition_on_magnitudes(shape, kshape, stride):
+    rng = np.random.default_rng(600 + shape[0] + kshape[1])
+    x = rng.uniform(-1, 1, shape).astype(np.float32)
+    f = rng.uniform(-1, 1, kshape).astype(np.float32)
+    if stride == 1:
+        assert np.array_equal(oracle.absdot2d(x, f), oracle.conv2d(np.abs(x), np.abs(f)))
+    assert np.array_equal(oracle.absdot2d_strided(x, f, stride), oracle.conv2d_strided(np.abs(x), np.abs(f), stride))
+
+
+class _TransposedScale:
+    """A planted mistake, kept on the CPU: the 2-D scale with the window read transposed (x[r+q][c+p]),
+    the kind of slip the single symmetric 2x2 value could not see."""
+    @staticmethod
+    def absdot2d(x, f):
+        x64, f64 = np.abs(np.asarray(x, np.float64)), np.abs(np.asarray(f, np.float64))
+        kh, kw = f64.shape
+        m = max(kh, kw)
+        oh, ow = x64.shape[0] - kh + 1, x64.shape[1] - kw + 1
+        xp = np.pad(x64, ((0, m), (0, m)))
+        return np.array([[sum(xp[r + q, c + p] * f64[p, q] for p in range(kh) for q in range(kw))
+                          for c in range(ow)] for r in range(oh)])
+
+    @staticmethod
+    def absdot2d_strided(x, f, stride):
+        return _TransposedScale.absdot2d(x, f)[::stride, ::stride]
+
+
+def test_scale_pins_catch_a_transposed_window():
+    img = np.array([[1, -2], [-3, 4]], np.float32)
+    sym = np.array([[-1, 1], [1, -1]], np.float32)
+    assert _TransposedScale.absdot2d(img, sym)[0, 0] == 10.0          # the symmetric case cannot tell
+    caught = 0
+    for kind, x, w, y, stride in _hand_cases():
+        if kind == "abs2d":
+            caught += not np.array_equal(_hand_eval(kind, x, w, stride, ora=_TransposedScale), y)
+    assert caught == 2                                                  # both hand-expanded scale cases can
+    rng = np.random.default_rng(77)
+    x = rng.uniform(-1, 1, (12, 15)).astype(np.float32)
+    f = rng.uniform(-1, 1, (2, 3)).astype(np.float32)
+    assert not np.array_equal(_TransposedScale.absdot2d(x, f), oracle.conv2d(np.abs(x), np.abs(f)))
+
+
+# ------------------------------------------------- rows further apart than wide
+@pytest.mark.parametrize("x_pitch,y_pitch", [(None, 40), (53, None), (61, 37), (48, 36)])
+def test_pitched_buffers_give_the_compact_result(x_pitch, y_pitch):
+    # 29 x 48 image, 3 x 13 filter -> 27 x 36 outputs.  The padding of the input holds NaN and the gaps of the
+    # result a sentinel (the wrapper checks they survive), so taking a pitch for a width, or the input pitch for
+    # the output pitch, cannot go unnoticed.
+    rng = np.random.default_rng(88)
+    x = rng.uniform(-1, 1, (29, 48)).astype(np.float32)
+    f = rng.uniform(-1, 1, (3, 13)).astype(np.float32)
+    for fn in (oracle.conv2d, oracle.absdot2d):
+        want = fn(x, f)
+        assert np.all(np.isfinite(want))
+        assert np.array_equal(fn(x, f, x_pitch=x_pitch, y_pitch=y_pitch), want)
+    for fn in (oracle.conv2d_strided, oracle.absdot2d_strided):
+        want = fn(x, f, 2)
+        yp = None if y_pitch is None else y_pitch - 18
+        assert np.array_equal(fn(x, f, 2, x_pitch=x_pitch, y_pitch=yp), want)
+    with pytest.raises(ValueError):
+        oracle.conv2d(x, f, x_pitch=47)
+    with pytest.raises(ValueError):
+        oracle.conv2d(x, f, y_pitch=35)
 
 
 def test_bad_arguments_raise():
