@@ -91,7 +91,8 @@ typedef enum {
     SYS_PROJ_SBM = 3,
     SYS_PROJ_BSM = 4,         /* 1-D only */
     SYS_PROJ_FSM = 5,         /* 1-D only */
-    SYS_PROJ_FFS = 6          /* 1-D only */
+    SYS_PROJ_FFS = 6,         /* 1-D only */
+    SYS_PROJ_MFMA = 7         /* 2-D only, never chosen by AUTO: see sys_conv2d          */
 } sys_projection_t;
 
 /* Limits.  Larger filters return SYS_ERR_UNSUPPORTED. */
@@ -194,8 +195,27 @@ int sys_conv1d_stt(const float *d_x, size_t n,
  *            (>= w-kw+1); elements between rows are left untouched
  *   projection  AUTO and FBS accept every filter in range (AUTO: BFS for square filters
  *            up to 7x7, SBM for 8x8 .. 11x11, FBS otherwise); BFS and SBM are built
- *            for a fixed list of filter sizes (sys_conv2d_has) and return
+ *            for SQUARE filters 2x2 .. 11x11 only (sys_conv2d_has) and return
  *            SYS_ERR_UNSUPPORTED otherwise; BSM, FSM and FFS are 1-D only.
+ *   h, w     at most INT_MAX - 2048 (SYS_ERR_UNSUPPORTED beyond; pitches at most 2^31).
+ *
+ * SYS_PROJ_MFMA (opt-in; any filter with kh, kw <= 13, square or not) leaves the paper's
+ * software arrays for the matrix cores: Section 6.2 / Table 5 observe that 2-D throughput
+ * collapses as the filter grows, and here an 11x11 filter is bound by the vector ALUs, not by
+ * memory.  Inputs and taps are split into two fp16 numbers each (hi + lo, 22 significant
+ * bits), three of the four partial products are accumulated in fp32 by
+ * v_mfma_f32_16x16x32_f16, and the result is fp32.  What the caller must know:
+ *   - every input must satisfy |x| < 8 (inputs are scaled by 2^13 before the split; a
+ *     larger value becomes infinite and turns the outputs it feeds into inf / NaN);
+ *     the taps are scaled by a power of two that the library derives from the largest
+ *     |f|, which must be 0 or lie within [1e-30, 1e30] (SYS_ERR_UNSUPPORTED otherwise);
+ *   - each input is represented to 2^-22 relative; inputs below 2^-27 (7.5e-9) in magnitude
+ *     count as zero, and so do taps below 2^-28 of the largest tap.  On data spread over
+ *     [0, 1] or [-1, 1] the results agree with the fp64 definition to about 1e-7 of
+ *     sum |f||x| (better than an fp32 chain of 121 multiply-adds).  The input range is a
+ *     promise the library cannot check, which is why AUTO never picks this path;
+ *   - a non-finite input (or tap) also spoils outputs outside its window, up to 18 rows
+ *     above / 3 below and 15 columns left / 3 right of it (0 * inf inside the blocked sums).
  */
 int sys_conv2d(const float *d_x, int h, int w, size_t x_pitch,
                const float *h_f, int kh, int kw,
@@ -240,7 +260,8 @@ int sys_copy_f32(const float *d_src, float *d_dst, size_t n, hipStream_t stream)
 const char *sys_status_string(int status);
 const char *sys_projection_name(int projection);
 
-/* hipError_t (as int) behind the calling thread's last SYS_ERR_HIP; 0 if none. */
+/* hipError_t (as int) behind the calling thread's most recent SYS_ERR_HIP; 0 if this thread
+ * has never seen one.  Later successful calls do not clear it. */
 int sys_last_hip_error(void);
 
 /* major*10000 + minor*100 + patch */

@@ -17,9 +17,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsysconv.so")
 
 SYS_OK, SYS_ERR_NULL, SYS_ERR_SIZE, SYS_ERR_ALIAS, SYS_ERR_UNSUPPORTED, SYS_ERR_HIP = range(6)
-SYS_PROJ_AUTO, SYS_PROJ_FBS, SYS_PROJ_BFS, SYS_PROJ_SBM, SYS_PROJ_BSM, SYS_PROJ_FSM, SYS_PROJ_FFS = range(7)
+(SYS_PROJ_AUTO, SYS_PROJ_FBS, SYS_PROJ_BFS, SYS_PROJ_SBM, SYS_PROJ_BSM, SYS_PROJ_FSM, SYS_PROJ_FFS,
+ SYS_PROJ_MFMA) = range(8)
 PROJECTIONS = {"AUTO": SYS_PROJ_AUTO, "FBS": SYS_PROJ_FBS, "BFS": SYS_PROJ_BFS, "SBM": SYS_PROJ_SBM,
-               "BSM": SYS_PROJ_BSM, "FSM": SYS_PROJ_FSM, "FFS": SYS_PROJ_FFS}
+               "BSM": SYS_PROJ_BSM, "FSM": SYS_PROJ_FSM, "FFS": SYS_PROJ_FFS, "MFMA": SYS_PROJ_MFMA}
 SYS_ERR_DESIGN = 6
 SYS_MAX_K1D = 64
 SYS_MAX_K2D = 15

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsysconv.so")
-SOURCES = ["api.hip", "conv1d.hip", "conv1d_arrays.hip", "conv1d_stride2.hip", "conv1d_stt.hip", "conv2d.hip", "conv2d_stride2.hip", "copy.hip"]
+SOURCES = ["api.hip", "conv1d.hip", "conv1d_arrays.hip", "conv1d_stride2.hip", "conv1d_stt.hip", "conv2d.hip", "conv2d_mfma.hip", "conv2d_stride2.hip", "copy.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

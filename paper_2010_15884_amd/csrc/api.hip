@@ -5,6 +5,7 @@
 
 #include "launch.h"
 
+#include <limits.h>
 #include <stdint.h>
 
 namespace {
@@ -26,10 +27,14 @@ bool ranges_overlap(const void* a, size_t a_bytes, const void* b, size_t b_bytes
 
 bool known_projection(int p)
 {
-    return p >= SYS_PROJ_AUTO && p <= SYS_PROJ_FFS;
+    return p >= SYS_PROJ_AUTO && p <= SYS_PROJ_MFMA;
 }
 
 bool misaligned(const void* p) { return ((uintptr_t)p & 3u) != 0; }
+
+// The 2-D kernels and their launchers round widths up to whole strips (at most 1024
+// columns) in int arithmetic; rows longer than this would overflow there.
+bool too_wide(int w) { return w > INT_MAX - 2048; }
 
 }  // namespace
 
@@ -137,7 +142,7 @@ int sys_conv1d_has(int projection, int k)
     case SYS_PROJ_FSM:
     case SYS_PROJ_FFS: return 1;
     case SYS_PROJ_BFS: return sysconv::has_conv1d_bfs(k) ? 1 : 0;
-    default: return 0;
+    default: return 0;                                                 // MFMA is 2-D only
     }
 }
 
@@ -149,6 +154,7 @@ int sys_conv2d_has(int projection, int kh, int kw)
     case SYS_PROJ_FBS: return 1;
     case SYS_PROJ_BFS: return sysconv::has_conv2d_bfs(kh, kw) ? 1 : 0;
     case SYS_PROJ_SBM: return sysconv::has_conv2d_sbm(kh, kw) ? 1 : 0;
+    case SYS_PROJ_MFMA: return sysconv::has_conv2d_mfma(kh, kw) ? 1 : 0;
     default: return 0;
     }
 }
@@ -162,7 +168,10 @@ int sys_conv2d(const float* d_x, int h, int w, size_t x_pitch, const float* h_f,
     if (x_pitch < (size_t)w || y_pitch < (size_t)ow) return SYS_ERR_SIZE;
     if (!known_projection(projection) || kh > SYS_MAX_K2D || kw > SYS_MAX_K2D) return SYS_ERR_UNSUPPORTED;
     if (misaligned(d_x) || misaligned(d_y)) return SYS_ERR_UNSUPPORTED;
-    if (x_pitch > ((size_t)1 << 31) || y_pitch > ((size_t)1 << 31)) return SYS_ERR_UNSUPPORTED;
+    if (too_wide(w) || x_pitch > ((size_t)1 << 31) || y_pitch > ((size_t)1 << 31)) return SYS_ERR_UNSUPPORTED;
+    if (projection == SYS_PROJ_MFMA
+        && (!sysconv::has_conv2d_mfma(kh, kw) || !sysconv::conv2d_mfma_taps_in_range(h_f, kh * kw)))
+        return SYS_ERR_UNSUPPORTED;
     const size_t x_bytes = ((size_t)(h - 1) * x_pitch + (size_t)w) * sizeof(float);
     const size_t y_bytes = ((size_t)(oh - 1) * y_pitch + (size_t)ow) * sizeof(float);
     if (ranges_overlap(d_x, x_bytes, d_y, y_bytes)) return SYS_ERR_ALIAS;
@@ -182,6 +191,8 @@ int sys_conv2d(const float* d_x, int h, int w, size_t x_pitch, const float* h_f,
     case SYS_PROJ_SBM:
         if (!sysconv::has_conv2d_sbm(kh, kw)) return SYS_ERR_UNSUPPORTED;
         return hip_status(sysconv::launch_conv2d_sbm(d_x, h, w, x_pitch, h_f, kh, kw, d_y, y_pitch, stream));
+    case SYS_PROJ_MFMA:                                                // size and tap range were checked above
+        return hip_status(sysconv::launch_conv2d_mfma(d_x, h, w, x_pitch, h_f, kh, kw, d_y, y_pitch, stream));
     default: return SYS_ERR_UNSUPPORTED;                               // BSM, FSM, FFS are 1-D only
     }
 }
@@ -197,7 +208,7 @@ int sys_conv2d_strided(const float* d_x, int h, int w, size_t x_pitch, const flo
     if (!known_projection(projection) || kh > SYS_MAX_K2D || kw > SYS_MAX_K2D) return SYS_ERR_UNSUPPORTED;
     if (!sys_conv2d_strided_has(projection, kh, kw, stride)) return SYS_ERR_UNSUPPORTED;
     if (misaligned(d_x) || misaligned(d_y)) return SYS_ERR_UNSUPPORTED;
-    if (x_pitch > ((size_t)1 << 31) || y_pitch > ((size_t)1 << 31)) return SYS_ERR_UNSUPPORTED;
+    if (too_wide(w) || x_pitch > ((size_t)1 << 31) || y_pitch > ((size_t)1 << 31)) return SYS_ERR_UNSUPPORTED;
     const size_t x_bytes = ((size_t)(h - 1) * x_pitch + (size_t)w) * sizeof(float);
     const size_t y_bytes = ((size_t)(oh - 1) * y_pitch + (size_t)ow) * sizeof(float);
     if (ranges_overlap(d_x, x_bytes, d_y, y_bytes)) return SYS_ERR_ALIAS;
@@ -244,12 +255,13 @@ const char* sys_projection_name(int projection)
     case SYS_PROJ_BSM: return "BSM";
     case SYS_PROJ_FSM: return "FSM";
     case SYS_PROJ_FFS: return "FFS";
+    case SYS_PROJ_MFMA: return "MFMA";
     default: return "?";
     }
 }
 
 int sys_last_hip_error(void) { return g_last_hip_error; }
 
-int sys_version(void) { return 100; }
+int sys_version(void) { return 200; }
 
 }  // extern "C"

@@ -64,6 +64,12 @@ bool has_conv2d_sbm(int kh, int kw);
 hipError_t launch_conv2d_sbm(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
                              float* y, size_t yp, hipStream_t s);
 
+// Matrix-core path (conv2d_mfma.hip): any filter up to 13 x 13.
+bool has_conv2d_mfma(int kh, int kw);
+bool conv2d_mfma_taps_in_range(const float* f, int n);      // largest |f| is 0 or within [1e-30, 1e30]
+hipError_t launch_conv2d_mfma(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
+                              float* y, size_t yp, hipStream_t s);
+
 hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s);
 
 }  // namespace sysconv

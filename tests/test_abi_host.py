@@ -33,7 +33,7 @@ def test_strings_and_version():
     for s in range(1, 6):
         assert B.status_string(s) not in ("ok", "unknown status")
     assert B.status_string(99) == "unknown status"
-    assert [B.projection_name(p) for p in range(7)] == ["AUTO", "FBS", "BFS", "SBM", "BSM", "FSM", "FFS"]
+    assert [B.projection_name(p) for p in range(8)] == ["AUTO", "FBS", "BFS", "SBM", "BSM", "FSM", "FFS", "MFMA"]
     assert B.projection_name(17) == "?"
 
 
@@ -55,7 +55,8 @@ X, Y = 0x10000000, 0x40000000
     ((X, 4, "w", 5, Y, 1), B.SYS_ERR_SIZE),
     ((X, 0, "w", 1, Y, 1), B.SYS_ERR_SIZE),
     ((X, 100, "w", 65, Y, 1), B.SYS_ERR_UNSUPPORTED),
-    ((X, 100, "w", 5, Y, 7), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, "w", 5, Y, 7), B.SYS_ERR_UNSUPPORTED),                     # MFMA is a 2-D projection
+    ((X, 100, "w", 5, Y, 8), B.SYS_ERR_UNSUPPORTED),
     ((X, 100, "w", 5, Y, -1), B.SYS_ERR_UNSUPPORTED),
     ((X + 2, 100, "w", 5, Y, 1), B.SYS_ERR_UNSUPPORTED),
     ((X, 100, "w", 5, X, 1), B.SYS_ERR_ALIAS),
@@ -86,11 +87,33 @@ def test_conv1d_validation(args, want):
     ((X, 100, 100, 100, "f", 4, 3, Y, 98, B.SYS_PROJ_BFS), B.SYS_ERR_UNSUPPORTED),
     ((X + 1, 100, 100, 100, "f", 3, 3, Y, 98, 1), B.SYS_ERR_UNSUPPORTED),
     ((X, 100, 100, 100, "f", 3, 3, X + 4 * 5000, 98, 1), B.SYS_ERR_ALIAS),
+    ((X, 100, 100, 100, "f", 14, 3, Y, 98, B.SYS_PROJ_MFMA), B.SYS_ERR_UNSUPPORTED),    # MFMA: up to 13 x 13
+    ((X, 100, 100, 100, "f", 3, 14, Y, 87, B.SYS_PROJ_MFMA), B.SYS_ERR_UNSUPPORTED),
+    ((X, 100, 100, 100, "f", 3, 3, X + 4 * 5000, 98, B.SYS_PROJ_MFMA), B.SYS_ERR_ALIAS),
+    # rows longer than INT_MAX - 2048 would overflow the kernels' strip arithmetic
+    ((X, 1, 2 ** 31 - 2047, 2 ** 31 - 2047, "f", 1, 3, 0x7000000000, 2 ** 31 - 2049, 1), B.SYS_ERR_UNSUPPORTED),
+    ((X, 1, 2 ** 31 - 1, 2 ** 31 - 1, "f", 1, 1, 0x7000000000, 2 ** 31 - 1, 0), B.SYS_ERR_UNSUPPORTED),
 ])
 def test_conv2d_validation(args, want):
     x, h, w, xp, f, kh, kw, y, yp, proj = args
     keep = np.ones(256, np.float32)
     got = B.lib().sys_conv2d(x, h, w, xp, keep.ctypes.data_as(FP) if f else None, kh, kw, y, yp, proj, None)
+    assert got == want, B.status_string(got)
+
+
+@pytest.mark.parametrize("amax,want", [(1e-33, B.SYS_ERR_UNSUPPORTED), (3e33, B.SYS_ERR_UNSUPPORTED),
+                                        (float("inf"), B.SYS_ERR_ALIAS), (0.0, B.SYS_ERR_ALIAS),
+                                        (1e-29, B.SYS_ERR_ALIAS), (1e29, B.SYS_ERR_ALIAS)])
+def test_mfma_tap_range_is_checked_before_any_launch(amax, want):
+    # The matrix-core path scales the taps by a power of two derived from the largest finite |f|, which has to lie
+    # in [1e-30, 1e30] (or be 0).  The check comes last, so filters that pass it run into the planted aliasing.
+    f = np.full(25, 0.0, np.float32)
+    f[7] = amax
+    f[3] = -amax / 2 if np.isfinite(amax) else 1.0
+    if not np.isfinite(amax):
+        f[7], f[3] = np.inf, 1e-33                 # a non-finite tap does not count; the largest finite one decides
+        want = B.SYS_ERR_UNSUPPORTED
+    got = B.lib().sys_conv2d(X, 100, 100, 100, f.ctypes.data_as(FP), 5, 5, X + 4 * 5000, 96, B.SYS_PROJ_MFMA, None)
     assert got == want, B.status_string(got)
 
 
@@ -109,6 +132,8 @@ def test_conv2d_has():
     assert B.sys_conv2d_has("BFS", 3, 3) and B.sys_conv2d_has("BFS", 5, 5) and B.sys_conv2d_has("BFS", 11, 11)
     assert not B.sys_conv2d_has("BFS", 4, 5) and not B.sys_conv2d_has("SBM", 12, 12)
     assert not B.sys_conv2d_has(42, 3, 3)
+    assert B.sys_conv2d_has("MFMA", 1, 1) and B.sys_conv2d_has("MFMA", 13, 13) and B.sys_conv2d_has("MFMA", 2, 13)
+    assert not B.sys_conv2d_has("MFMA", 14, 3) and not B.sys_conv2d_has("MFMA", 3, 14)
 
 
 def test_binding_rejects_host_tensors():
