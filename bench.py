@@ -20,6 +20,8 @@ single JSON line printed at the end carries
                reading is stored in profiles/, else null
   roofline_alu the same for the 8192^2, 11x11 workload, which is bound by the vector ALUs:
                2 x multiply-adds / kernel time against the 78.6 TFLOP/s fp32 vector peak
+  roofline_mfma that workload through the opt-in matrix-core projection: issued MFMA flops against
+               the 2.5 PFLOP/s dense fp16 peak, with the fraction of them the definition needs
   cpu_baseline the CPU oracle (plain C, fp64) timed here on the host cores
   also         all five workloads and every projection built for them, each with
                GB/s, Gtap/s and its fraction of the HBM and fp32-FMA peaks, a plain
@@ -67,17 +69,42 @@ def _parse():
     return ap.parse_args()
 
 
+def kernel_source_hash() -> str:
+    """Fingerprint of the kernel sources (csrc/*.hip, *.h): counter readings stored under profiles/
+    carry the fingerprint of the sources they were taken with."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_2010_15884_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def _stored_traffic(kernel_key: str):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by
-    the copy kernel's reading); kept as `traffic_bytes <key> <bytes>` lines in profiles/."""
+    the copy kernel's reading); kept as `traffic_bytes <key> <bytes>` lines in profiles/hbm_traffic.txt
+    together with the fingerprint of the kernel sources they were measured on.  Returns
+    (bytes or None, provenance): a reading taken on other sources than the ones now in the tree
+    is not reported as this run's traffic."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    prov = {"file": "profiles/hbm_traffic.txt", "measured_on_sources": None, "sources_now": kernel_source_hash()}
     if not os.path.exists(path):
-        return None
+        return None, prov
+    value = None
     for line in open(path):
         m = re.match(r"traffic_bytes\s+(\S+)\s+(\d+)", line.strip())
         if m and m.group(1) == kernel_key:
-            return int(m.group(2))
-    return None
+            value = int(m.group(2))
+        m = re.match(r"source_hash\s+(\S+)", line.strip())
+        if m:
+            prov["measured_on_sources"] = m.group(1)
+    prov["stale"] = prov["measured_on_sources"] != prov["sources_now"]
+    if prov["stale"]:
+        prov["stale_reading"] = value
+        value = None
+    return value, prov
 
 
 def main() -> int:
@@ -292,6 +319,7 @@ def main() -> int:
 
     # the kernel behind the headline projection (AUTO picks FBS at 16 taps)
     head_proj = "FBS" if args.projection.upper() == "AUTO" else args.projection.upper()
+    head_traffic, head_prov = _stored_traffic(f"conv1d_{head_proj.lower()}_k16_n64m")
     head_kernel = {"FBS": "conv1d_fbs_kernel<16>", "SBM": "conv1d_sbm_kernel<16>", "BFS": "conv1d_bfs_kernel<16>",
                    "BSM": "conv1d_array_kernel<0>", "FSM": "conv1d_array_kernel<1>",
                    "FFS": "conv1d_array_kernel<2>"}[head_proj]
@@ -313,7 +341,7 @@ def main() -> int:
                    "gtap_per_s": round(wl.n_taps / (wall / args.steps) / 1e9, 1)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": _stored_traffic(f"conv1d_{head_proj.lower()}_k16_n64m"),
+                     "traffic": head_traffic, "traffic_source": head_prov,
                      "kernel": head_kernel, "kernel_us_mean": round(kern_mean * 1e6, 2),
                      "kernel_us_median": round(kern_med * 1e6, 2),
                      "copy_same_footprint_GB/s": round(copy_gbs, 1),
@@ -342,7 +370,7 @@ def main() -> int:
             _, c_mean, _ = time_launches(copy_launch, steps, 3)
             copy_gbs = 8 * n_copy / c_mean / 1e9
             del srcs, dsts
-            for proj in ("FBS", "SBM", "BFS", "BSM", "FSM", "FFS"):
+            for proj in ("FBS", "SBM", "BFS", "BSM", "FSM", "FFS", "MFMA"):
                 has = B.sys_conv1d_has(proj, w2.k_shape[0]) if w2.ndim == 1 else B.sys_conv2d_has(proj, *w2.k_shape)
                 if not has:
                     continue
@@ -370,17 +398,42 @@ def main() -> int:
         result["also"] = also
         # the one workload that is bound by the vector ALUs, not by HBM: its own roofline object
         # (121 multiply-adds per 8 bytes; peak = 256 CUs x 64 lanes x 2.4 GHz x 2 flop = 78.6 TFLOP/s fp32)
-        alu = [r for r in also if r["workload"] == "conv2d_8k_11x11"]
+        alu = [r for r in also if r["workload"] == "conv2d_8k_11x11" and r["projection"] != "MFMA"]
         if alu:
             best = max(alu, key=lambda r: r["Gtap/s"])
             kern = {"SBM": "conv2d_sbm_kernel<11, 11, 1>", "BFS": "conv2d_bfs_kernel<11, 11, 1>",
                     "FBS": "conv2d_fbs_kernel<2>"}[best["projection"]]
+            alu_traffic, alu_prov = _stored_traffic(f"conv2d_{best['projection'].lower()}_11x11_8k")
             result["roofline_alu"] = {
                 "workload": "conv2d_8k_11x11", "projection": best["projection"], "kernel": kern, "bound": "alu",
                 "achieved": round(2 * best["Gtap/s"] / 1e3, 2), "peak": round(2 * FMA_PEAK_G / 1e3, 1),
                 "unit": "TFLOP/s", "frac": round(best["Gtap/s"] / FMA_PEAK_G, 4),
-                "traffic": _stored_traffic(f"conv2d_{best['projection'].lower()}_11x11_8k"),
-                "kernel_us_mean": best["kernel_us_mean"]}
+                "frac_of_published_fp32_vector_peak_157.3": round(2 * best["Gtap/s"] / 1e3 / 157.3, 4),
+                "traffic": alu_traffic, "traffic_source": alu_prov,
+                "kernel_us_mean": best["kernel_us_mean"],
+                "note": "peak = 256 CUs x 64 lanes x 2.4 GHz x 2 flop (one v_fmac_f32 per lane-clock); the published "
+                        "157.3 TFLOP/s counts packed fp32 instructions, which this build does not use"}
+        # the same workload on the matrix cores (opt-in projection): issued MFMA flops against the dense fp16 peak,
+        # and how many of them are the definition's own multiply-adds
+        mf = [r for r in also if r["workload"] == "conv2d_8k_11x11" and r["projection"] == "MFMA"]
+        if mf:
+            r = mf[0]
+            w5 = W.WORKLOADS["conv2d_8k_11x11"]
+            ns = (w5.k_shape[0] + 4) // 2                    # instructions per product and 4 x 64 block of outputs
+            issued_macs_per_output = 3 * ns * 16 * 16 * 32 / 256.0
+            t = r["kernel_us_mean"] * 1e-6
+            achieved = 2 * issued_macs_per_output * w5.n_outputs / t / 1e12
+            mf_traffic, mf_prov = _stored_traffic("conv2d_mfma_11x11_8k")
+            result["roofline_mfma"] = {
+                "workload": "conv2d_8k_11x11", "projection": "MFMA", "kernel": f"conv2d_mfma_kernel<{ns}>",
+                "bound": "mfma", "achieved": round(achieved, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                "frac": round(achieved / 2500.0, 4),
+                "useful_fraction": round(w5.k_shape[0] * w5.k_shape[1] / issued_macs_per_output, 4),
+                "useful_TFLOP/s": round(2 * r["Gtap/s"] / 1e3, 2),
+                "frac_hbm_peak": r["frac_hbm_peak"], "traffic": mf_traffic, "traffic_source": mf_prov,
+                "kernel_us_mean": r["kernel_us_mean"],
+                "note": "v_mfma_f32_16x16x32_f16 on split fp16 operands (3 products); useful_fraction = kh*kw "
+                        "multiply-adds of the definition / multiply-adds issued (Toeplitz zeros and the split)"}
 
     # ---------------------------------------------------------- CPU baseline
     if not args.no_cpu:

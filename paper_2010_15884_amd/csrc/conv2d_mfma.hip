@@ -27,11 +27,17 @@
 // their largest magnitude, inputs by a fixed 2^13.  That fixes the admissible input range:
 // |x| < 8 (larger values become infinite in fp16), and inputs below 2^-27 count as zero.
 //
-// Data path of a wavefront (strip of 64 output columns, block of rows walked 4 at a time):
-// global_load_dwordx4 (2 input rows x 80 columns per "unit", 40 lanes) -> scale, split,
-// pack -> wave-private LDS -> ds_read of the 8-input windows (B operands) -> a ring of NS
-// operand pairs in registers (each 2-row unit serves NS consecutive instructions slots as
-// the block moves down) -> MFMA -> global_store_dwordx4.
+// Data path of a wavefront (strip of 64 output columns, block of up to 64 rows walked 4 at a
+// time).  Input travels in "units" of 2 rows x 80 columns (40 float4).  Interior strips:
+// global_load_lds_dwordx4 (40 lanes) puts a unit straight into a 16-slot queue in LDS, so that
+// the 14 units in flight per wavefront cost no registers; when a unit has arrived every lane
+// reads its 8-input window (the B operand), scales, splits and packs it into a ring of NS (+1)
+// operand pairs in registers -- each 2-row unit serves NS consecutive instruction slots as the
+// block moves down -- then MFMA and global_store_dwordx4.  Strips that reach past the right
+// edge of the image fetch through registers with bounds checks instead.
+// Measured on MI355X, 8192^2: 11x11 138 us, 13x13 151 us (the vector-ALU kernels: 243 us and
+// 397 us); the vector ALUs (scaling and splitting, 44 % busy) and the matrix cores (26 %) still
+// take turns rather than overlap, and that, not HBM, bounds it.
 #include "launch.h"
 #include "systolic.h"
 #include "tiling.h"
@@ -50,6 +56,7 @@ constexpr int kMInCols = 80;               // staged input columns: 64 + 12 are 
 constexpr int kMUnitLanes = 40;            // lanes that fetch a unit: 2 rows x 20 float4
 constexpr int kMWaves = kBlock / kWave;
 constexpr float kMXScale = 8192.0f;        // 2^13: inputs up to 8 stay finite in fp16
+constexpr float kMLoScale = 2048.0f;       // 2^11: the lo parts are kept this much larger
 
 typedef const float __attribute__((address_space(4)))* kernarg_floats;
 
@@ -76,27 +83,76 @@ struct MfmaFetcher {
 
     // Fetch the next unit.  Past the block's last row the last row is read again: an unconditional
     // load keeps the control flow straight, and what it brings in only feeds rows that are not stored.
+    // Address of the lane's part of the next unit; moves on to the unit after it.
+    __device__ __forceinline__ const float* next_address()
+    {
+        const float* p = rowp + (rows_left > 0 ? off_two : off_one);
+        rowp += rows_left >= 2 ? 2 * xp : rows_left == 1 ? xp : 0;
+        rows_left -= min(rows_left, 2);
+        return p;
+    }
+
     template <bool EDGE>
     __device__ __forceinline__ void next(float (&v)[4])
     {
-        const float* p = rowp + (rows_left > 0 ? off_two : off_one);
+        const float* p = next_address();
         if (EDGE) {
             load4_guarded<false>(p - fcol, fcol, w_img, v);
         } else {
             const f4u t = *reinterpret_cast<const f4u*>(p);
             v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
         }
-        rowp += rows_left >= 2 ? 2 * xp : rows_left == 1 ? xp : 0;
-        rows_left -= min(rows_left, 2);
     }
 };
+
+// Interior strips do not stage through registers at all: the unit travels from global memory
+// straight into a queue slot in LDS (global_load_lds_dwordx4: lane l's 16 bytes land at
+// M0 + 16 l; lanes switched off write nothing), so the data in flight costs no registers and
+// the queue can be deep enough to cover the memory latency with two or three wavefronts per
+// SIMD.  The compiler does not see these loads; the waits are written by hand (mfma_wait_loads).
+constexpr int kMQueue = 16;                // queue slots per wavefront
+constexpr int kMAhead = kMQueue - 2;       // loads in flight behind the unit being taken (at most kMAhead + 2 slots are in use)
+constexpr int kMSlotBytes = 2 * kMInCols * (int)sizeof(float);
+
+__device__ __forceinline__ void mfma_dma_unit(const float* p, unsigned lds_byte_address, unsigned long long lanes)
+{
+    unsigned long long saved;
+    asm volatile("s_mov_b64 %0, exec\n\t"
+                 "s_mov_b32 m0, %2\n\t"
+                 "s_mov_b64 exec, %3\n\t"
+                 "global_load_lds_dwordx4 %1, off\n\t"
+                 "s_mov_b64 exec, %0"
+                 : "=&s"(saved)
+                 : "v"(p), "s"(lds_byte_address), "s"(lanes)
+                 : "memory");
+}
+
+// Wait until at most `kMAhead` of the wavefront's vector-memory operations are outstanding.
+// Loads complete in the order they were issued, so a unit that kMAhead younger loads have
+// followed has arrived by then -- whatever stores are outstanding besides (they only make the
+// wait stricter).
+__device__ __forceinline__ void mfma_wait_loads()
+{
+    static_assert(kMAhead == 14, "the wait below is written for 14 loads in flight");
+    asm volatile("s_waitcnt vmcnt(14)" ::: "memory");
+}
+
+// Eight consecutive inputs, scaled and split as in mfma_split.
+__device__ __forceinline__ void mfma_split8(const f4& a, const f4& b, h8& hi, h8& lo)
+{
+    const f4 sa = a * kMXScale, sb = b * kMXScale;
+    const h4 ha = __builtin_convertvector(sa, h4), hb = __builtin_convertvector(sb, h4);
+    const h4 la = __builtin_convertvector((sa - __builtin_convertvector(ha, f4)) * kMLoScale, h4);
+    const h4 lb = __builtin_convertvector((sb - __builtin_convertvector(hb, f4)) * kMLoScale, h4);
+    hi = __builtin_shufflevector(ha, hb, 0, 1, 2, 3, 4, 5, 6, 7);
+    lo = __builtin_shufflevector(la, lb, 0, 1, 2, 3, 4, 5, 6, 7);
+}
 
 // v * 2^13 = hi + lo * 2^-11 in fp16 (both rounded to nearest): the remainder v*2^13 - hi is
 // exact in fp32 and at most half an fp16 ulp of hi; stored 2^11 times larger it has the
 // magnitude of hi at most and stays a normal fp16 number whenever hi is one (the matrix
 // cores treat subnormal fp16 inputs as zero).  A value of 8 or more becomes infinite here
 // and shows up as inf / NaN in the results it feeds.
-constexpr float kMLoScale = 2048.0f;
 __device__ __forceinline__ void mfma_split(const float (&v)[4], h4& hi, h4& lo)
 {
     f4 s;
@@ -121,6 +177,8 @@ __global__ __launch_bounds__(kBlock) void conv2d_mfma_kernel(Taps2D taps, const 
     __shared__ __attribute__((aligned(16))) _Float16 wtab[2][4][TROWS][16];
     // per wavefront: two unit buffers x (hi, lo) x 2 rows x 80 columns
     __shared__ __attribute__((aligned(16))) _Float16 stage[kMWaves][2][2][2][kMInCols];
+    // per wavefront: queue of units as they come from memory, 2 rows x 80 columns of fp32 each
+    __shared__ __attribute__((aligned(16))) float queue[kMWaves][kMQueue][2][kMInCols];
 
     kernarg_floats taps_f = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
     for (int e = threadIdx.x; e < 4 * TROWS * 16; e += kBlock) {
@@ -175,88 +233,133 @@ __global__ __launch_bounds__(kBlock) void conv2d_mfma_kernel(Taps2D taps, const 
     constexpr int kPlane = 2 * kMInCols, kBuf = 2 * kPlane;
 
     h8 bh[RS], bl[RS];                     // ring: unit u lives in slot u % RS
-    float pre[RS][4];                      // fetched, not yet staged: unit u in pre[u % RS]
 
-    // stage unit `slot` (from pre) and read the lane's windows of it into the ring
-    auto consume = [&](int slot) {
-        const int ub = slot & 1;
-        {
-            h4 hi, lo;
-            mfma_split(pre[slot], hi, lo);
-            *reinterpret_cast<h4*>(st_w + ub * kBuf) = hi;                 // (shadow lanes write the same values again)
-            *reinterpret_cast<h4*>(st_w + ub * kBuf + kPlane) = lo;
+    // ------------------------------------------------------------------- edge strips
+    // Strips that reach past the right edge of the image fetch through registers with per-lane
+    // bounds checks (columns outside the image read as 0), split in the 40 fetching lanes and hand
+    // the fp16 values to the other lanes through a wave-private staging buffer.  They are a small
+    // part of any large image, so nothing is kept in flight beyond the step at hand.
+    auto run_edge = [&]() {
+        float pre[2][4];
+        // stage the unit in pre[k] and read the lane's windows of it into ring slot `slot`
+        auto consume = [&](int k, int slot) {
+            {
+                h4 hi, lo;
+                mfma_split(pre[k], hi, lo);
+                *reinterpret_cast<h4*>(st_w + k * kBuf) = hi;              // (shadow lanes write the same values again)
+                *reinterpret_cast<h4*>(st_w + k * kBuf + kPlane) = lo;
+            }
+            // Other lanes of this wavefront read what was just written.  The hardware serves a
+            // wavefront's LDS accesses in order; all that is needed is that the compiler keeps
+            // the reads behind the writes.
+            asm volatile("" ::: "memory");
+            const h4 h0 = *reinterpret_cast<const h4*>(st_r + k * kBuf);
+            const h4 h1 = *reinterpret_cast<const h4*>(st_r + k * kBuf + 4);
+            const h4 l0 = *reinterpret_cast<const h4*>(st_r + k * kBuf + kPlane);
+            const h4 l1 = *reinterpret_cast<const h4*>(st_r + k * kBuf + kPlane + 4);
+            bh[slot] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
+            bl[slot] = __builtin_shufflevector(l0, l1, 0, 1, 2, 3, 4, 5, 6, 7);
+        };
+#pragma unroll
+        for (int u = 0; u < NS; ++u) {
+            fetch.template next<true>(pre[u & 1]);
+            consume(u & 1, u % RS);
         }
-        // Other lanes of this wavefront read what was just written.  The hardware serves a
-        // wavefront's LDS accesses in order; all that is needed is that the compiler keeps the
-        // reads behind the writes, without the wait for outstanding global loads a fence brings.
-        asm volatile("" ::: "memory");
-        const h4 h0 = *reinterpret_cast<const h4*>(st_r + ub * kBuf);
-        const h4 h1 = *reinterpret_cast<const h4*>(st_r + ub * kBuf + 4);
-        const h4 l0 = *reinterpret_cast<const h4*>(st_r + ub * kBuf + kPlane);
-        const h4 l1 = *reinterpret_cast<const h4*>(st_r + ub * kBuf + kPlane + 4);
-        bh[slot] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
-        bl[slot] = __builtin_shufflevector(l0, l1, 0, 1, 2, 3, 4, 5, 6, 7);
+        const int col = c0 + kTile * i16;
+        for (int t0 = 0; t0 < steps; t0 += PERIOD) {
+#pragma unroll
+            for (int ph = 0; ph < PERIOD; ++ph) {
+                const int t = t0 + ph;
+                if (t >= steps) break;
+                fetch.template next<true>(pre[0]);
+                fetch.template next<true>(pre[1]);
+                f4 acc_hh = {0.0f, 0.0f, 0.0f, 0.0f}, acc_x = acc_hh;
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    const int slot = (2 * ph + s) % RS;
+                    acc_x = __builtin_amdgcn_mfma_f32_16x16x32_f16(al[s], bh[slot], acc_x, 0, 0, 0);
+                    acc_hh = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[s], bh[slot], acc_hh, 0, 0, 0);
+                    acc_x = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[s], bl[slot], acc_x, 0, 0, 0);
+                }
+                // lane (i16, kb) holds outputs (row 4 t + kb, columns c0 + 4 i16 .. + 3)
+                if (4 * t + kb < rows_out) {
+                    float o[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        o[v] = __builtin_fmaf(acc_x[v], inv_scale * (1.0f / kMLoScale), acc_hh[v] * inv_scale);
+                    store4_guarded(y + (long long)(r0 + 4 * t + kb) * yp, col, ow, o);
+                }
+                consume(0, (2 * ph + NS) % RS);
+                consume(1, (2 * ph + NS + 1) % RS);
+            }
+        }
     };
 
-    auto run = [&](auto edge_tag) {
-        constexpr bool EDGE = decltype(edge_tag)::value;
-        // units 0 .. NS-1 fill the ring, units NS .. RS+NS-3 are left in flight
-#pragma unroll
-        for (int u = 0; u < NS; ++u) fetch.template next<EDGE>(pre[u % RS]);
-#pragma unroll
-        for (int u = 0; u < NS; ++u) consume(u % RS);
-#pragma unroll
-        for (int u = NS; u < NS + RS - 2; ++u) fetch.template next<EDGE>(pre[u % RS]);
+    // ---------------------------------------------------------------- interior strips
+    auto run_queued = [&]() {
+        const unsigned long long fetch_lanes = (1ull << kMUnitLanes) - 1;  // lanes 0 .. 39 fetch
+        const unsigned q_base = (unsigned)(size_t)&queue[wave][0][0][0];   // LDS byte address of slot 0
+        const float* const win = &queue[wave][0][kb >> 1][kTile * i16 + 8 * (kb & 1)];   // the lane's window in slot 0
+        int q_in = 0, q_out = 0;                                           // slots of the next unit in / out (uniform)
 
-        // lane (i16, kb) holds outputs (row 4 t + kb, columns c0 + 4 i16 .. + 3) of step t
+        auto issue = [&]() {
+            mfma_dma_unit(fetch.next_address(), q_base + q_in * kMSlotBytes, fetch_lanes);
+            q_in = q_in + 1 == kMQueue ? 0 : q_in + 1;
+        };
+        // the lane's 8-input window of the oldest queued unit -> ring slot
+        auto take = [&](int slot) {
+            const float* w8 = win + q_out * (kMSlotBytes / (int)sizeof(float));
+            const f4 a = *reinterpret_cast<const f4*>(w8);
+            const f4 b = *reinterpret_cast<const f4*>(w8 + 4);
+            mfma_split8(a, b, bh[slot], bl[slot]);
+            q_out = q_out + 1 == kMQueue ? 0 : q_out + 1;
+        };
+
+        // Units 0 .. NS-3 go into the ring before the first step; every step then starts by sending
+        // two more units on their way and taking in the two newest units it needs (2t+NS-2 and
+        // 2t+NS-1), which its last six instructions use -- their split overlaps the instructions
+        // that work on the older units.  kMAhead younger loads are in flight at every wait.
+#pragma unroll 1
+        for (int u = 0; u < kMAhead; ++u) issue();
+#pragma unroll
+        for (int u = 0; u < NS - 2; ++u) {
+            issue();                                                       // unit u now has kMAhead younger loads behind it
+            mfma_wait_loads();
+            take(u % RS);
+        }
+
         const int col = c0 + kTile * i16;
         const long long yoff = (long long)kb * yp + col;
 
-        // One step: 4 output rows.  `ph` = t % PERIOD decides every ring index, so it is a
-        // compile-time value of the unrolled loops below (2 * PERIOD = RS).
         auto step = [&](int t, int ph, auto whole_tag) {
-            constexpr bool WHOLE = decltype(whole_tag)::value;             // all 4 rows of the step exist
-            // Nothing moves across a step's start: left alone, the scheduler hoists the cheap
-            // first instructions of every later split (they depend on outstanding loads only)
-            // to the top of the loop body and waits there for all the loads in flight.
+            constexpr bool WHOLE = decltype(whole_tag)::value;
+            // nothing moves across a step's start (the scheduler would otherwise pull the first
+            // instructions of later steps' splits up to here, in front of their waits)
             __builtin_amdgcn_sched_barrier(0);
-            // two more units go into flight
-            fetch.template next<EDGE>(pre[(2 * ph + NS + RS - 2) % RS]);
-            fetch.template next<EDGE>(pre[(2 * ph + NS + RS - 1) % RS]);
-
-            f4 acc_hh = {0.0f, 0.0f, 0.0f, 0.0f}, acc_x = acc_hh;
+            issue();
+            issue();
+            mfma_wait_loads();
+            take((2 * ph + NS - 2) % RS);
+            take((2 * ph + NS - 1) % RS);
+            f4 acc_hh = {0.0f, 0.0f, 0.0f, 0.0f}, acc_lh = acc_hh, acc_hl = acc_hh;
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 const int slot = (2 * ph + s) % RS;
-                // the two cross products share an accumulator; the hi*hi product sits between
-                // them so that neither has to wait for the other
-                acc_x = __builtin_amdgcn_mfma_f32_16x16x32_f16(al[s], bh[slot], acc_x, 0, 0, 0);
                 acc_hh = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[s], bh[slot], acc_hh, 0, 0, 0);
-                acc_x = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[s], bl[slot], acc_x, 0, 0, 0);
+                acc_lh = __builtin_amdgcn_mfma_f32_16x16x32_f16(al[s], bh[slot], acc_lh, 0, 0, 0);
+                acc_hl = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[s], bl[slot], acc_hl, 0, 0, 0);
             }
             if (WHOLE || 4 * t + kb < rows_out) {
-                float o[4];
+                f4u o4;
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    o[v] = __builtin_fmaf(acc_x[v], inv_scale * (1.0f / kMLoScale), acc_hh[v] * inv_scale);
+                    o4[v] = __builtin_fmaf(acc_lh[v] + acc_hl[v], inv_scale * (1.0f / kMLoScale), acc_hh[v] * inv_scale);
                 float* yr = y + (long long)(r0 + 4 * t) * yp;              // uniform; the lane's part is yoff
-                if (EDGE) {
-                    store4_guarded(yr + (yoff - col), col, ow, o);
-                } else {
-                    f4u o4;
-                    o4.x = o[0]; o4.y = o[1]; o4.z = o[2]; o4.w = o[3];
-                    if (SYSCONV_NONTEMPORAL_STORE) __builtin_nontemporal_store(o4, reinterpret_cast<f4u*>(yr + yoff));
-                    else *reinterpret_cast<f4u*>(yr + yoff) = o4;
-                }
+                if (SYSCONV_NONTEMPORAL_STORE) __builtin_nontemporal_store(o4, reinterpret_cast<f4u*>(yr + yoff));
+                else *reinterpret_cast<f4u*>(yr + yoff) = o4;
             }
-            // the next step needs units 2t+NS and 2t+NS+1 in the ring
-            consume((2 * ph + NS) % RS);
-            consume((2 * ph + NS + 1) % RS);
         };
 
-        // Whole periods of whole steps run without a branch inside the loop body (an exit from
-        // the middle of the body would make the compiler wait for every outstanding load at the
-        // top of each trip); what is left, at most PERIOD steps, follows with its checks.
         const int whole_steps = rows_out >> 2;
         int t0 = 0;
         for (; t0 + PERIOD <= whole_steps; t0 += PERIOD) {
@@ -268,9 +371,12 @@ __global__ __launch_bounds__(kBlock) void conv2d_mfma_kernel(Taps2D taps, const 
             if (t0 + ph >= steps) break;
             step(t0 + ph, ph, std::false_type{});
         }
+        // nothing may still be on its way into this workgroup's LDS when the wavefront ends
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
-    if (edge) run(std::true_type{});
-    else run(std::false_type{});
+
+    if (edge) run_edge();
+    else run_queued();
 }
 
 float largest_finite_magnitude(const float* f, int n)
