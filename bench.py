@@ -66,6 +66,11 @@ def _parse():
                          "(671 M outputs), 1-D k in {2, 5} at stride 1 (six designs) and stride 2 (FBS), 2-D 2x2 and "
                          "5x5 at stride 1 (SBM, FBS, BFS) and stride 2 (FBS); throughput = outputs / time, as in the "
                          "paper; prints JSON")
+    ap.add_argument("--size-sweep", action="store_true",
+                    help="only time the 5x5 convolution (every projection built for it) and a plain copy of the same "
+                         "footprint on square images from 2048^2 to 16384^2, and fit time = t0 + bytes / rate to each: "
+                         "how much of the 4096^2 workload's time is start-up and tail, and what rate the kernels "
+                         "approach on large images; prints JSON")
     return ap.parse_args()
 
 
@@ -177,6 +182,57 @@ def main() -> int:
         per_batch = sorted(evs[bi].elapsed_time(evs[bi + 1]) * 1e-3 / (bounds[bi + 1] - bounds[bi])
                            for bi in range(n_batches))
         return wall, total / steps, per_batch[len(per_batch) // 2]
+
+    if args.size_sweep:
+        sides = (2048, 2896, 4096, 5792, 8192, 11584, 16384)
+        base = W.WORKLOADS["conv2d_4k_5x5"]
+        series = {}
+        rows = []
+        for side in sides:
+            wk = W.Workload(f"conv2d_{side}_5x5", 2, (side, side), base.k_shape, base.x_range, base.w_range, base.seed)
+            nrot = rotation(wk)
+            g = torch.Generator(device="cuda")
+            g.manual_seed(base.seed)
+            dxs = [torch.empty(wk.x_shape, dtype=torch.float32, device="cuda").uniform_(0.0, 1.0, generator=g)
+                   for _ in range(nrot)]
+            dys = [torch.empty(wk.y_shape, dtype=torch.float32, device="cuda") for _ in range(nrot)]
+            _, taps = W.make(base, x_shape=(8, 8))
+            st = {"i": 0}
+            n_copy = wk.algorithmic_bytes // 8
+            flat_src = [d.view(-1)[:n_copy] for d in dxs]
+            flat_dst = [torch.empty(n_copy, dtype=torch.float32, device="cuda") for _ in range(nrot)]
+
+            def copy_launch():
+                i = st["i"] = (st["i"] + 1) % nrot
+                B.sys_copy_f32(flat_src[i], flat_dst[i])
+            steps = 40 if side <= 8192 else 12
+            _, c_mean, _ = time_launches(copy_launch, steps, 3)
+            row = {"side": side, "algorithmic_bytes": wk.algorithmic_bytes, "copy_us": round(c_mean * 1e6, 2)}
+            series.setdefault("copy", []).append((wk.algorithmic_bytes, c_mean))
+            del flat_dst
+            for proj in ("BFS", "SBM", "FBS", "MFMA"):
+                def launch():
+                    i = st["i"] = (st["i"] + 1) % nrot
+                    B.sys_conv2d(dxs[i], taps, dys[i], projection=proj)
+                _, k_mean, _ = time_launches(launch, steps, 3)
+                row[f"{proj}_us"] = round(k_mean * 1e6, 2)
+                row[f"{proj}_frac_hbm_peak"] = round(wk.algorithmic_bytes / k_mean / 1e9 / HBM_PEAK_GBS, 4)
+                series.setdefault(proj, []).append((wk.algorithmic_bytes, k_mean))
+            rows.append(row)
+            print(json.dumps(row), file=sys.stderr, flush=True)
+            del dxs, dys, flat_src
+            torch.cuda.empty_cache()
+        fits = {}
+        for name, pts in series.items():
+            b = np.array([p[0] for p in pts], dtype=np.float64)
+            t = np.array([p[1] for p in pts], dtype=np.float64)
+            slope, t0 = np.polyfit(b, t, 1)                      # t = t0 + bytes * slope
+            fits[name] = {"t0_us": round(t0 * 1e6, 2), "rate_GB/s": round(1e-9 / slope, 1),
+                          "rate_frac_hbm_peak": round(1e-9 / slope / HBM_PEAK_GBS, 4),
+                          "max_residual_us": round(float(np.max(np.abs(t - (t0 + slope * b)))) * 1e6, 2)}
+        print(json.dumps({"size_sweep_5x5": rows, "fit": fits, "data": "synthetic (uniform fp32 drawn on the device)",
+                          "note": "least-squares fit of kernel time = t0 + algorithmic bytes / rate over the seven sizes"}))
+        return 0
 
     if args.design_space:
         from paper_2010_15884_amd import schedule_model as sm

@@ -50,6 +50,30 @@ __device__ __forceinline__ bool wave_tile(int per_xcd, int row_blocks, int strip
     return rb < row_blocks;
 }
 
+// The other arrangement: the four wavefronts of a workgroup take four horizontally adjacent
+// strips of ONE row block (a 1024-column piece of ROWS rows), and workgroups walk down such a
+// column of pieces before moving to the next.  The halo columns of a strip are the first
+// columns of its right neighbour; here three of four such neighbours are in the same workgroup,
+// so the cache line they share is fetched from memory once.
+__device__ __forceinline__ bool wave_tile_wide(int per_xcd, int row_blocks, int strips, int& rb, int& strip)
+{
+    constexpr int kWaves = kBlock / kWave;
+    const int g = xcd_contiguous(blockIdx.x, per_xcd);
+    const int strip_groups = (strips + kWaves - 1) / kWaves;
+    if (g >= row_blocks * strip_groups) return false;
+    const int sg = g / row_blocks;
+    rb = g - sg * row_blocks;
+    strip = sg * kWaves + wave_in_block();
+    return strip < strips;
+}
+
+inline long long tile_workgroups_wide(int row_blocks, int strips, long long& per_xcd)
+{
+    const long long groups = (long long)row_blocks * ((strips + (kBlock / kWave) - 1) / (kBlock / kWave));
+    per_xcd = (groups + kXcds - 1) / kXcds;
+    return per_xcd * kXcds;
+}
+
 // Strips per band, from in-process A/B runs on MI355X (block-form BFS, 5x5 unless noted;
 // us with 1 / 16 strips per band):
 //   pitch 16 KB (4096^2) 28.6 / 33.2, 20 KB 46 / 48, 24 KB and 28 KB level,
