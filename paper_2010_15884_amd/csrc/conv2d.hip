@@ -112,6 +112,95 @@ __global__ __launch_bounds__(kBlock) void conv2d_fbs_kernel(const float* __restr
 // reads become scalar loads).
 typedef const float __attribute__((address_space(4)))* kernarg_floats;
 
+// The same design with the filter size known at compile time (has_conv2d_fbs_static): every loop
+// below is unrolled, the taps sit in SGPRs for the whole kernel, and the 1-D passes are taken
+// input row by input row -- the array hands a staged row's inputs on from PE to PE once
+// (KW-1 DPP moves) and each of the up to min(RPW, KH) output rows that the input row feeds
+// takes its KW products from that one window, so the hand-overs are shared between the 1-D
+// convolutions instead of repeated per filter row.
+// Lanes of a strip that keep their results.  Single-row filters move as many bytes as a copy, and
+// there strips that start on 64-byte boundaries measure faster (8192^2, 1x5: 98.8 -> 91.5 us), as in
+// the 1-D kernels; with taller filters the rounding does not pay.
+__host__ __device__ constexpr int fbs_static_valid_lanes(int kh, int kw)
+{
+    return kh == 1 ? ((kWave - halo_lanes(kw)) & ~3) : kWave - halo_lanes(kw);
+}
+
+template <int KH, int KW, int RPW>
+__global__ __launch_bounds__(kBlock) void conv2d_fbs_static_kernel(Taps2D taps, const float* __restrict__ x,
+                                                                   float* __restrict__ y, int h, int w_img,
+                                                                   long long xp, int oh, int ow, long long yp,
+                                                                   int tiles_y, int n_tiles, int side, int per_xcd)
+{
+    (void)taps;
+    constexpr int kTileRows = RPW * (kBlock / kWave);                      // output rows per workgroup
+    constexpr int kInRows = kTileRows + KH - 1;
+    __shared__ __attribute__((aligned(16))) float tile[kInRows * kStrip];
+    kernarg_floats taps_f = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
+
+    const int t = xcd_contiguous(blockIdx.x, per_xcd);
+    if (t >= n_tiles) return;                                              // whole workgroup leaves together
+    int tile_y, tile_x;
+    band_order(t, tiles_y, n_tiles / tiles_y, side, tile_y, tile_x);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = wave_in_block();
+    constexpr int valid_lanes = fbs_static_valid_lanes(KH, KW);
+    const int col0 = tile_x * kTile * valid_lanes;
+    const int row0 = tile_y * kTileRows;
+
+    // stage: wavefront v copies input rows v, v+4, ... of the tile; all its loads go out first
+    const int last_row = h - 1 - row0;                                     // rows past the image repeat its last row
+    constexpr int kPerWave = (kInRows + 3) / 4;
+    float stage[kPerWave][4];
+#pragma unroll
+    for (int k = 0; k < kPerWave; ++k)
+        load4_guarded<false>(x + (long long)(row0 + min(wave + 4 * k, last_row)) * xp, col0 + kTile * lane, w_img,
+                             stage[k]);
+#pragma unroll
+    for (int k = 0; k < kPerWave; ++k) {
+        const int rr = wave + 4 * k;
+        if (rr < kInRows) {
+            f4 t4;
+            t4.x = stage[k][0]; t4.y = stage[k][1]; t4.z = stage[k][2]; t4.w = stage[k][3];
+            *reinterpret_cast<f4*>(tile + rr * kStrip + kTile * lane) = t4;
+        }
+    }
+    __syncthreads();
+
+    float acc[RPW][4];
+    const int lrow0 = wave * RPW;
+#pragma unroll
+    for (int rho = 0; rho < RPW + KH - 1; ++rho) {
+        float win[KW + 3];
+        const f4 t4 = *reinterpret_cast<const f4*>(tile + (lrow0 + rho) * kStrip + kTile * lane);
+        win[0] = t4.x; win[1] = t4.y; win[2] = t4.z; win[3] = t4.w;
+#pragma unroll
+        for (int m = 4; m < KW + 3; ++m) win[m] = from_lane_above(win[m - 4]);   // X(c) <- X(c+1), once per row
+#pragma unroll
+        for (int j = 0; j < RPW; ++j) {
+            const int p = rho - j;                                         // compile-time
+            if (p < 0 || p >= KH) continue;
+#pragma unroll
+            for (int q = 0; q < KW; ++q) {
+                const float wv = taps_f[p * KW + q];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (p == 0 && q == 0) acc[j][i] = wv * win[i];
+                    else acc[j][i] = __builtin_fmaf(wv, win[q + i], acc[j][i]);
+                }
+            }
+        }
+    }
+
+    if (lane < valid_lanes) {
+#pragma unroll
+        for (int j = 0; j < RPW; ++j) {
+            const int r = row0 + lrow0 + j;
+            if (r < oh) store4_guarded(y + (long long)r * yp, col0 + kTile * lane, ow, acc[j]);
+        }
+    }
+}
+
 // A zero the optimiser cannot see through (one SALU move).
 __device__ __forceinline__ int opaque_zero()
 {
@@ -707,9 +796,66 @@ hipError_t launch_fbs_tiles(const float* x, int h, int w, size_t xp, const float
 }
 }  // namespace
 
+namespace {
+template <int KH, int KW, int RPW>
+hipError_t launch_fbs_static(const float* x, int h, int w, size_t xp, const float* f, float* y, size_t yp,
+                             hipStream_t s)
+{
+    constexpr int tile_rows = RPW * (kBlock / kWave);
+    Taps2D taps;
+    fill_taps(taps, f, KH * KW);
+    const int oh = h - KH + 1, ow = w - KW + 1;
+    const int cols = kTile * fbs_static_valid_lanes(KH, KW);
+    const int tiles_x = (ow + cols - 1) / cols;
+    const int tiles_y = (oh + tile_rows - 1) / tile_rows;
+    const long long n_tiles = (long long)tiles_x * tiles_y;
+    const long long per_xcd = (n_tiles + kXcds - 1) / kXcds;
+    const long long blocks = per_xcd * kXcds;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((conv2d_fbs_static_kernel<KH, KW, RPW>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
+                       taps, x, y, h, w, (long long)xp, oh, ow, (long long)yp, tiles_y, (int)n_tiles,
+                       band_width(xp), (int)per_xcd);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Filters whose size is known at compile time: square 2x2 .. 7x7, single rows 1 x 2..11 and
+// single columns 2..11 x 1 (the two passes of a separable filter).  From 8x8 on the taps no longer
+// fit the scalar registers and the unrolled form loses to the run-time-sized kernel (11x11 on
+// 8192^2: 353 us with 4 rows per wavefront, 423 us with 2, against 313 us).  Output rows per wavefront
+// from a sweep on MI355X (us with 1 / 2 / 3 / 4 rows): 4096^2 3x3 27.1 / 26.4 / 28.0 / 28.2,
+// 5x5 32.3 / 27.7 / 28.1 / 29.6, 7x7 51.7 / 41.2 / 42.1 / 39.6; 8192^2 5x5 115.5 / 95.3 / 96.8 / 102.2.
+bool has_conv2d_fbs_static(int kh, int kw)
+{
+    if (kh == kw) return kh >= 2 && kh <= 7;
+    return (kh == 1 && kw >= 2 && kw <= 11) || (kw == 1 && kh >= 2 && kh <= 11);
+}
+
+namespace {
+#define SYSCONV_FBS_STATIC(KH, KW, RPW) \
+    if (kh == KH && kw == KW) return launch_fbs_static<KH, KW, RPW>(x, h, w, xp, f, y, yp, s)
+
+hipError_t launch_fbs_static_any(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw, float* y,
+                                 size_t yp, hipStream_t s)
+{
+    SYSCONV_FBS_STATIC(2, 2, 2); SYSCONV_FBS_STATIC(3, 3, 2); SYSCONV_FBS_STATIC(4, 4, 2); SYSCONV_FBS_STATIC(5, 5, 2);
+    SYSCONV_FBS_STATIC(6, 6, 4); SYSCONV_FBS_STATIC(7, 7, 4);
+    SYSCONV_FBS_STATIC(1, 2, 4); SYSCONV_FBS_STATIC(1, 3, 4); SYSCONV_FBS_STATIC(1, 4, 4); SYSCONV_FBS_STATIC(1, 5, 4);
+    SYSCONV_FBS_STATIC(1, 6, 4); SYSCONV_FBS_STATIC(1, 7, 4); SYSCONV_FBS_STATIC(1, 8, 4); SYSCONV_FBS_STATIC(1, 9, 4);
+    SYSCONV_FBS_STATIC(1, 10, 4); SYSCONV_FBS_STATIC(1, 11, 4);
+    SYSCONV_FBS_STATIC(2, 1, 4); SYSCONV_FBS_STATIC(3, 1, 4); SYSCONV_FBS_STATIC(4, 1, 4); SYSCONV_FBS_STATIC(5, 1, 4);
+    SYSCONV_FBS_STATIC(6, 1, 4); SYSCONV_FBS_STATIC(7, 1, 4); SYSCONV_FBS_STATIC(8, 1, 4); SYSCONV_FBS_STATIC(9, 1, 4);
+    SYSCONV_FBS_STATIC(10, 1, 4); SYSCONV_FBS_STATIC(11, 1, 4);
+    return hipErrorInvalidValue;
+}
+#undef SYSCONV_FBS_STATIC
+}  // namespace
+
 hipError_t launch_conv2d_fbs(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
                              float* y, size_t yp, hipStream_t s)
 {
+    if (has_conv2d_fbs_static(kh, kw)) return launch_fbs_static_any(x, h, w, xp, f, kh, kw, y, yp, s);
     // Output rows per wavefront, measured on MI355X with 1, 2, 3, 4, 6 and 8 (us):
     //   4096^2 5x5   50.7  38.6  34.9  36.9  39.8  43.5      8192^2 5x5    178  127  122  121  125  134
     //   4096^2 7x7   63.3  50.1  48.6  49.9  53.3   -        8192^2 11x11  374  313  313  313  334  349

@@ -57,6 +57,7 @@ hipError_t launch_conv2d_fbs(const float* x, int h, int w, size_t xp, const floa
                              float* y, size_t yp, hipStream_t s);
 hipError_t launch_conv2d_fbs_stride2(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
                                      float* y, size_t yp, hipStream_t s);
+bool has_conv2d_fbs_static(int kh, int kw);      // sizes the FBS tile kernel is specialised for
 bool has_conv2d_bfs(int kh, int kw);
 hipError_t launch_conv2d_bfs(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw,
                              float* y, size_t yp, hipStream_t s);

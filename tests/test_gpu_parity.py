@@ -117,6 +117,23 @@ def test_conv2d_random_all_sizes(kshape):
             assert e <= TOL, f"{proj} {kh}x{kw} image {h}x{w}: rel err {e}"
 
 
+@pytest.mark.parametrize("k", range(2, 12))
+def test_conv2d_single_row_and_single_column_filters(k):
+    # 1 x k and k x 1 (the two passes of a separable filter) run kernels of their own: strips of 4 * (64 - halo) columns,
+    # rounded down to whole 64-byte pieces for single rows, 16 output rows per workgroup
+    for (kh, kw) in [(1, k), (k, 1)]:
+        strip = 4 * ((64 - (kw + 2) // 4) & ~3 if kh == 1 else 64)
+        for (h, w) in [(kh, kw), (kh + 15, kw + strip - 1), (kh + 16, kw + strip), (kh + 33, kw + 2 * strip + 3), (131, 1031)]:
+            x, f = W.random_case(h * 100 + w + k, (h, w), (kh, kw), x_range=(0.0, 1.0))
+            for proj in ("FBS", "AUTO"):
+                y = run2d(x, f, proj)
+                assert y.shape == (h - kh + 1, w - kw + 1)
+                e = err2d(y, x, f)
+                assert e <= TOL, f"{proj} {kh}x{kw} image {h}x{w}: rel err {e}"
+        xi, fi = W.integer_case(k, (70, 600), (kh, kw), x_max=9, w_max=5)
+        assert np.array_equal(run2d(xi, fi, "FBS").astype(np.float64), oracle.conv2d(xi, fi)), f"{kh}x{kw}"
+
+
 @pytest.mark.parametrize("kk", [2, 3, 5, 6, 7, 8, 9, 11])
 def test_conv2d_tall_images_cover_every_item_height(kk):
     # The strip kernels give a wavefront 2 ... 16 output rows, fewer on images that would not yield 4096
