@@ -62,6 +62,44 @@ def build_c_demo(verbose: bool = True) -> str:
     return exe
 
 
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+HOST_LOGIC = ["api.hip", "conv1d_stt.hip", "conv2d_mfma.hip"]      # argument checks, the design planner, the tap scaling
+
+
+def build_host_sanitized(verbose: bool = True) -> str:
+    """Host code of the library under AddressSanitizer + UndefinedBehaviorSanitizer (the device code is
+    compiled as always): the translation units that hold host logic are rebuilt with the sanitizers on the
+    host pass only, linked with the ordinary objects of the rest and with tests/abi_san_driver.cpp into an
+    executable that needs no GPU."""
+    san_dir = os.path.join(OBJ, "san")
+    os.makedirs(san_dir, exist_ok=True)
+    objs = []
+    for src in SOURCES:
+        if src in HOST_LOGIC:
+            obj = os.path.join(san_dir, src.replace(".hip", ".o"))
+            cmd = ["hipcc", *[f for f in FLAGS if f != "-O3"], "-O1", *SAN_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+            res = subprocess.run(cmd, capture_output=True, text=True)
+            if res.returncode != 0:
+                raise RuntimeError(f"hipcc (host sanitizers) failed on {src}:\n{res.stderr}")
+        else:
+            obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+            if not os.path.exists(obj):
+                _compile(src)
+        objs.append(obj)
+    exe = os.path.join(san_dir, "abi_san_driver")
+    driver = os.path.join(ROOT, "tests", "abi_san_driver.cpp")
+    cmd = ["hipcc", "--offload-arch=gfx950", "-std=c++17", "-O1", "-g", "-fsanitize=address", "-fsanitize=undefined",
+           "-fno-sanitize-recover=all", "-fno-gpu-sanitize", "-I", os.path.join(ROOT, "include"), "-x", "c++", driver,
+           "-x", "none", *objs, "-o", exe]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"link of the sanitized host build failed:\n{res.stderr}")
+    if verbose:
+        print(f"built {exe}")
+    return exe
+
+
 if __name__ == "__main__":
     build()
     build_c_demo()

@@ -101,7 +101,10 @@ __global__ __launch_bounds__(kBlock) void conv1d_stt_kernel(Taps1D taps, const f
     }
 }
 
-int iabs(int v) { return v < 0 ? -v : v; }
+// |v| > limit without negating v (INT_MIN has no negative)
+bool beyond(int v, int limit) { return v > limit || v < -limit; }
+
+int iabs(int v) { return v < 0 ? -v : v; }                               // for values already known to be small
 
 }  // namespace
 
@@ -111,10 +114,10 @@ SttVerdict plan_stt(const int alloc[2], const int sched[2], bool x_on, const int
 {
     const int p0 = alloc[0], p1 = alloc[1], s0 = sched[0], s1 = sched[1];
     for (int v : {p0, p1, s0, s1})
-        if (iabs(v) > kWave) return kSttTooLarge;
+        if (beyond(v, kWave)) return kSttTooLarge;
     // the recurrences themselves: X must be handed on between points that read the same
     // input (c+q constant), W between points with the same tap, Z along the taps
-    if (x_on && (ex[0] + ex[1] != 0 || ex[0] == 0)) return kSttBadDependence;
+    if (x_on && ((long long)ex[0] + ex[1] != 0 || ex[0] == 0)) return kSttBadDependence;
     if (w_on && (ew[1] != 0 || ew[0] == 0)) return kSttBadDependence;
     if (ez[0] != 0 || (ez[1] != 1 && ez[1] != -1)) return kSttBadDependence;
     // two points on one PE must differ in time
@@ -128,11 +131,11 @@ SttVerdict plan_stt(const int alloc[2], const int sched[2], bool x_on, const int
     bool far = false;
     for (const Dep& d : deps) {
         if (!d.on) continue;
-        if (iabs(d.e[0]) > kWave || iabs(d.e[1]) > kWave) return kSttTooLarge;
+        if (beyond(d.e[0], kWave) || beyond(d.e[1], kWave)) return kSttTooLarge;
         *d.dl = p0 * d.e[0] + p1 * d.e[1];                                 // space distance P.e
         *d.dt = s0 * d.e[0] + s1 * d.e[1];                                 // time distance s.e
         if (*d.dt < 1) return kSttNotCausal;                               // a value would be read before it exists
-        if (iabs(*d.dl) > 1 || *d.dt > kSttDepth) far = true;
+        if (beyond(*d.dl, 1) || *d.dt > kSttDepth) far = true;
     }
     if (det != 1 && det != -1) return kSttTooLarge;                        // idle holes in the PE-time grid: not built
     if (far) return kSttTooLarge;                                          // only nearest-neighbour moves, short histories

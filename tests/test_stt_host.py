@@ -69,3 +69,14 @@ def test_conv1d_stt_validation(args, want):
     got = B.lib().sys_conv1d_stt(x, n, keep.ctypes.data_as(FP) if w else None, k, y,
                                  ctypes.byref(d) if d is not None else None, None)
     assert got == want, B.status_string(got)
+
+
+def test_extreme_coefficients_are_refused_without_overflow():
+    # INT_MIN has no negative and INT_MAX + INT_MAX no sum: the planner must refuse such designs by comparison, not
+    # by arithmetic on them (the sanitized build in tests/test_sanitizers.py shows there is no overflow on the way)
+    lo, hi = -2 ** 31, 2 ** 31 - 1
+    for design in [((hi, 1), (lo, 1), None, None, (0, 1)), ((lo, lo), (hi, hi), (hi, lo), (lo, 0), (0, 1)),
+                   ((1, 0), (0, 1), (hi, hi), None, (0, 1)), ((1, 0), (0, 1), (lo, lo), None, (0, 1)),
+                   ((1, 0), (1, 1), None, (lo, 0), (0, 1)), ((1, 0), (1, 1), None, None, (0, lo))]:
+        got = B.sys_stt_check(B.stt_design(*design), 5)
+        assert got in (B.SYS_ERR_UNSUPPORTED, B.SYS_ERR_DESIGN), B.status_string(got)
