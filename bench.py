@@ -460,11 +460,21 @@ def main() -> int:
             kern = {"SBM": "conv2d_sbm_kernel<11, 11, 1>", "BFS": "conv2d_bfs_kernel<11, 11, 1>",
                     "FBS": "conv2d_fbs_kernel<2>"}[best["projection"]]
             alu_traffic, alu_prov = _stored_traffic(f"conv2d_{best['projection'].lower()}_11x11_8k")
+            # what the vector ALUs sustain with nothing in the way: the register-only yard-stick, 8 wavefronts per SIMD
+            ybuf = torch.empty(2048 * 256, dtype=torch.float32, device="cuda")
+            fmas = {"n": 0}
+
+            def alu_launch():
+                fmas["n"] = B.sys_alu_yardstick_f32(ybuf, 2048, 500)
+            _, y_mean, _ = time_launches(alu_launch, 10, 2)
+            yard_g = fmas["n"] / y_mean / 1e9
             result["roofline_alu"] = {
                 "workload": "conv2d_8k_11x11", "projection": best["projection"], "kernel": kern, "bound": "alu",
                 "achieved": round(2 * best["Gtap/s"] / 1e3, 2), "peak": round(2 * FMA_PEAK_G / 1e3, 1),
                 "unit": "TFLOP/s", "frac": round(best["Gtap/s"] / FMA_PEAK_G, 4),
                 "frac_of_published_fp32_vector_peak_157.3": round(2 * best["Gtap/s"] / 1e3 / 157.3, 4),
+                "measured_fmac_yardstick_TFLOP/s": round(2 * yard_g / 1e3, 2),
+                "frac_of_measured_yardstick": round(best["Gtap/s"] / yard_g, 4),
                 "traffic": alu_traffic, "traffic_source": alu_prov,
                 "kernel_us_mean": best["kernel_us_mean"],
                 "note": "peak = 256 CUs x 64 lanes x 2.4 GHz x 2 flop (one v_fmac_f32 per lane-clock); the published "

@@ -261,6 +261,17 @@ int sys_conv2d_has(int projection, int kh, int kw);
  */
 int sys_copy_f32(const float *d_src, float *d_dst, size_t n, hipStream_t stream);
 
+/*
+ * The vector-ALU counterpart of sys_copy_f32: a register-only loop of fp32 multiply-adds (taps in
+ * scalar registers, as in the convolution kernels), `workgroups` x 256 lanes x `trips` x 256
+ * multiply-adds.  The benchmark prints its rate beside the ALU-bound 11x11 row: what the vector
+ * ALUs of this part sustain with one v_fmac_f32 per lane and clock.
+ *   d_out  device, workgroups * 256 floats (written: one value per lane)
+ * Returns the number of multiply-adds enqueued, or minus a sys_status_t on error
+ * (workgroups and trips must lie in 1 .. 2^20).
+ */
+long long sys_alu_yardstick_f32(float *d_out, int workgroups, int trips, hipStream_t stream);
+
 const char *sys_status_string(int status);
 const char *sys_projection_name(int projection);
 

@@ -26,7 +26,7 @@ SYS_MAX_K1D = 64
 SYS_MAX_K2D = 15
 
 EXPORTS = ["sys_conv1d", "sys_conv1d_strided", "sys_conv2d", "sys_conv1d_has", "sys_conv1d_strided_has",
-           "sys_conv2d_has", "sys_conv2d_strided", "sys_conv2d_strided_has", "sys_stt_check", "sys_conv1d_stt", "sys_copy_f32", "sys_status_string",
+           "sys_conv2d_has", "sys_conv2d_strided", "sys_conv2d_strided_has", "sys_stt_check", "sys_conv1d_stt", "sys_copy_f32", "sys_alu_yardstick_f32", "sys_status_string",
            "sys_projection_name", "sys_last_hip_error", "sys_version"]
 
 _lib = None
@@ -103,6 +103,8 @@ def lib() -> ctypes.CDLL:
         L.sys_conv2d_has.restype = ci
         L.sys_copy_f32.argtypes = [vp, vp, sz, vp]
         L.sys_copy_f32.restype = ci
+        L.sys_alu_yardstick_f32.argtypes = [vp, ci, ci, vp]
+        L.sys_alu_yardstick_f32.restype = ctypes.c_longlong
         L.sys_status_string.argtypes = [ci]
         L.sys_status_string.restype = ctypes.c_char_p
         L.sys_projection_name.argtypes = [ci]
@@ -296,6 +298,17 @@ def sys_copy_f32(d_src, d_dst, stream=None):
         raise ValueError("copy needs two contiguous tensors of equal size")
     _check(lib().sys_copy_f32(d_src.data_ptr(), d_dst.data_ptr(), d_src.numel(), _stream_handle(stream)))
     return d_dst
+
+
+def sys_alu_yardstick_f32(d_out, workgroups: int, trips: int, stream=None) -> int:
+    """Enqueue the register-only multiply-add loop; returns the number of multiply-adds it performs."""
+    _device_f32(d_out, "d_out")
+    if not d_out.is_contiguous() or d_out.numel() < int(workgroups) * 256:
+        raise ValueError("d_out must be contiguous with room for workgroups * 256 floats")
+    n = int(lib().sys_alu_yardstick_f32(d_out.data_ptr(), int(workgroups), int(trips), _stream_handle(stream)))
+    if n < 0:
+        _check(-n)
+    return n
 
 
 def sys_version() -> int:

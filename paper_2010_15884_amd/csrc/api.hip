@@ -231,6 +231,15 @@ int sys_copy_f32(const float* d_src, float* d_dst, size_t n, hipStream_t stream)
     return hip_status(sysconv::launch_copy_f32(d_src, d_dst, n, stream));
 }
 
+long long sys_alu_yardstick_f32(float* d_out, int workgroups, int trips, hipStream_t stream)
+{
+    if (!d_out) return -(long long)SYS_ERR_NULL;
+    if (workgroups < 1 || trips < 1 || workgroups > (1 << 20) || trips > (1 << 20)) return -(long long)SYS_ERR_SIZE;
+    if (misaligned(d_out)) return -(long long)SYS_ERR_UNSUPPORTED;
+    const int st = hip_status(sysconv::launch_alu_yardstick(d_out, workgroups, trips, stream));
+    return st == SYS_OK ? sysconv::alu_yardstick_fmas(workgroups, trips) : -(long long)st;
+}
+
 const char* sys_status_string(int status)
 {
     switch (status) {

@@ -72,5 +72,7 @@ hipError_t launch_conv2d_mfma(const float* x, int h, int w, size_t xp, const flo
                               float* y, size_t yp, hipStream_t s);
 
 hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s);
+hipError_t launch_alu_yardstick(float* out, int workgroups, int trips, hipStream_t s);
+long long alu_yardstick_fmas(int workgroups, int trips);
 
 }  // namespace sysconv

@@ -126,6 +126,15 @@ def test_copy_validation():
     assert L.sys_copy_f32(X + 1, Y, 10, None) == B.SYS_ERR_UNSUPPORTED
 
 
+def test_alu_yardstick_validation():
+    L = B.lib()
+    assert L.sys_alu_yardstick_f32(None, 8, 8, None) == -B.SYS_ERR_NULL
+    assert L.sys_alu_yardstick_f32(Y, 0, 8, None) == -B.SYS_ERR_SIZE
+    assert L.sys_alu_yardstick_f32(Y, 8, 0, None) == -B.SYS_ERR_SIZE
+    assert L.sys_alu_yardstick_f32(Y, (1 << 20) + 1, 8, None) == -B.SYS_ERR_SIZE
+    assert L.sys_alu_yardstick_f32(Y + 2, 8, 8, None) == -B.SYS_ERR_UNSUPPORTED
+
+
 def test_conv2d_has():
     assert B.sys_conv2d_has("FBS", 15, 15) and B.sys_conv2d_has("AUTO", 1, 9)
     assert not B.sys_conv2d_has("FBS", 16, 3)

@@ -204,6 +204,19 @@ def test_copy_kernel():
         assert torch.equal(a, b[:n]) and float(b[n:].abs().sum()) == 0.0
 
 
+def test_alu_yardstick_runs_and_counts_its_multiply_adds():
+    out = torch.full((4 * 256 + 8,), float("nan"), dtype=torch.float32, device="cuda")
+    n = B.sys_alu_yardstick_f32(out[:4 * 256], 4, 3)
+    torch.cuda.synchronize()
+    assert n == 4 * 256 * 3 * 256
+    res = out.cpu().numpy()
+    assert np.isfinite(res[:4 * 256]).all() and np.isnan(res[4 * 256:]).all()
+    # every workgroup does the same arithmetic: lane l of each holds the same value
+    assert np.array_equal(res[:256], res[256:512]) and np.array_equal(res[:256], res[768:1024])
+    with pytest.raises(ValueError):
+        B.sys_alu_yardstick_f32(out[:100], 4, 3)
+
+
 def test_runs_on_a_side_stream():
     s = torch.cuda.Stream()
     x, w = W.random_case(4, (100000,), (16,))
