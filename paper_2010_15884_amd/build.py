@@ -21,12 +21,16 @@ SOURCES = ["api.hip", "conv1d.hip", "conv1d_arrays.hip", "conv1d_stride2.hip", "
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+# Per-file additions.  The matrix-core kernel keeps its accumulators in ordinary vector registers
+# (the results go straight to the vector ALUs; from accumulation registers every value would
+# first need a v_accvgpr_read).
+FILE_FLAGS = {"conv2d_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
     extra = os.environ.get("SYSCONV_EXTRA_FLAGS", "").split()      # build-time tunables (-DSYSCONV_...)
-    cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc", *FLAGS, *FILE_FLAGS.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)

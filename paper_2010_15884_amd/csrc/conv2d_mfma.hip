@@ -27,17 +27,26 @@
 // their largest magnitude, inputs by a fixed 2^13.  That fixes the admissible input range:
 // |x| < 8 (larger values become infinite in fp16), and inputs below 2^-27 count as zero.
 //
-// Data path of a wavefront (strip of 64 output columns, block of up to 64 rows walked 4 at a
-// time).  Input travels in "units" of 2 rows x 80 columns (40 float4).  Interior strips:
-// global_load_lds_dwordx4 (40 lanes) puts a unit straight into a 16-slot queue in LDS, so that
-// the 14 units in flight per wavefront cost no registers; when a unit has arrived every lane
-// reads its 8-input window (the B operand), scales, splits and packs it into a ring of NS (+1)
-// operand pairs in registers -- each 2-row unit serves NS consecutive instruction slots as the
-// block moves down -- then MFMA and global_store_dwordx4.  Strips that reach past the right
-// edge of the image fetch through registers with bounds checks instead.
-// Measured on MI355X, 8192^2: 11x11 138 us, 13x13 151 us (the vector-ALU kernels: 243 us and
-// 397 us); the vector ALUs (scaling and splitting, 44 % busy) and the matrix cores (26 %) still
-// take turns rather than overlap, and that, not HBM, bounds it.
+// Data path.  A column group is 256 output columns, computed by 4 wavefronts (a strip of 64
+// columns each) that walk a block of rows 4 rows at a time.  Input travels in "units" of 2 rows
+// x 272 columns.  The four wavefronts take turns fetching units with global_load_lds_dwordx4:
+// whole-wavefront loads of 1 KB per row straight into a 16-slot queue in LDS that all four read,
+// so that the 12 units in flight cost no registers.  When a unit has arrived (a wait on the
+// fetching wavefront's own loads, then a workgroup barrier) every lane reads its 8-input window
+// (the B operand), scales, splits and packs it into a ring of NS (+1) operand pairs in registers
+// -- each 2-row unit serves NS consecutive instruction slots as the block moves down -- then
+// MFMA and global_store_dwordx4.  The column group at the right edge of the image runs the same
+// code with the lanes beyond the image switched off in the loads (their queue entries stay 0)
+// and column checks in the stores.
+//
+// Launch shape.  Measured on MI355X: workgroups that share a CU do not advance at the same rate
+// (of three 4-wavefront workgroups started together the first ends after 77 us, the last after
+// 113 us, on an 8192^2 image), and the stragglers run with too few wavefronts to keep HBM busy.
+// So a workgroup is three column groups wide (12 wavefronts, the whole CU) and its barrier keeps
+// them in step; the row blocks are sized so that the grid is one round of resident workgroups:
+// set-up and pipeline fill are paid once, nothing starts late.  8192^2: 11x11 114 - 125 us,
+// 13x13 119 - 126 us, 3x3 106 us (a copy of the same bytes: 86 us; the vector-ALU kernels take
+// 243 us for 11x11); with 4-wavefront workgroups of 64 rows, many rounds: 138 us and 151 us.
 #include "launch.h"
 #include "systolic.h"
 #include "tiling.h"
@@ -52,11 +61,11 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMOutCols = 64;              // output columns of a wavefront's strip: 16 bases x 4
-constexpr int kMInCols = 80;               // staged input columns: 64 + 12 are read, 20 float4 are fetched
-constexpr int kMUnitLanes = 40;            // lanes that fetch a unit: 2 rows x 20 float4
 constexpr int kMWaves = kBlock / kWave;
+constexpr int kMGroupCols = kMWaves * kMOutCols;   // output columns of a workgroup
 constexpr float kMXScale = 8192.0f;        // 2^13: inputs up to 8 stay finite in fp16
 constexpr float kMLoScale = 2048.0f;       // 2^11: the lo parts are kept this much larger
+constexpr int kMaxDevices = 64;            // devices whose occupancy answer is remembered
 
 typedef const float __attribute__((address_space(4)))* kernarg_floats;
 
@@ -68,53 +77,26 @@ struct MfmaShape {
     static constexpr int TROWS = 2 * NS + 3;       // rows of the tap tables: dr - jr + 3 = 0 .. 2 NS + 2
 };
 
-// Where a lane fetches its share of a unit (two consecutive input rows, 80 columns = 40 float4;
-// lanes 40 .. 63 repeat the work of lanes 0 .. 23, so that no lane is switched off and the
-// fetches need no branch).  Units are fetched in order; everything but the lane's two offsets
-// is uniform across the wavefront and advances with scalar arithmetic.
-struct MfmaFetcher {
-    const float* __restrict__ rowp;  // first row of the next unit (uniform)
-    long long xp;
-    int w_img;
-    int rows_left;            // rows of the block that lie beyond the next unit's first row (uniform)
-    int fcol;                 // first of the lane's four input columns
-    long long off_two;        // lane's offset from the unit's first row when the unit has both rows
-    long long off_one;        // ... when its second row lies beyond the block (it repeats the first)
+// The queue of units in LDS.  A slot, in floats: [0, 256) first row, [256, 512) second row,
+// [512, 528) and [528, 544) the 16 halo columns of the two rows, [544, 548) a pad that takes
+// the loads issued only to keep the count of loads per unit fixed.
+constexpr int kSQueue = 16;                // slots
+constexpr int kSAhead = 12;                // units in flight behind the two being taken; every wavefront owns a quarter
+constexpr int kSCols = kMGroupCols + 16;   // input columns of a unit (a filter is at most 13 wide: 256 + 12 are read)
+constexpr int kSPad = 2 * kSCols;          // float offset of the pad
+constexpr int kSSlotFloats = 2 * kSCols + 4;
+constexpr unsigned kSSlotBytes = kSSlotFloats * sizeof(float);
+static_assert(kSQueue >= kSAhead + 4, "a slot is written again only after the barrier that follows its last reader");
 
-    // Fetch the next unit.  Past the block's last row the last row is read again: an unconditional
-    // load keeps the control flow straight, and what it brings in only feeds rows that are not stored.
-    // Address of the lane's part of the next unit; moves on to the unit after it.
-    __device__ __forceinline__ const float* next_address()
-    {
-        const float* p = rowp + (rows_left > 0 ? off_two : off_one);
-        rowp += rows_left >= 2 ? 2 * xp : rows_left == 1 ? xp : 0;
-        rows_left -= min(rows_left, 2);
-        return p;
-    }
+__device__ __forceinline__ int shared_slot_offset(int row, int col)
+{
+    return col < kMGroupCols ? row * kMGroupCols + col : 2 * kMGroupCols + row * 16 + (col - kMGroupCols);
+}
 
-    template <bool EDGE>
-    __device__ __forceinline__ void next(float (&v)[4])
-    {
-        const float* p = next_address();
-        if (EDGE) {
-            load4_guarded<false>(p - fcol, fcol, w_img, v);
-        } else {
-            const f4u t = *reinterpret_cast<const f4u*>(p);
-            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-        }
-    }
-};
-
-// Interior strips do not stage through registers at all: the unit travels from global memory
-// straight into a queue slot in LDS (global_load_lds_dwordx4: lane l's 16 bytes land at
-// M0 + 16 l; lanes switched off write nothing), so the data in flight costs no registers and
-// the queue can be deep enough to cover the memory latency with two or three wavefronts per
-// SIMD.  The compiler does not see these loads; the waits are written by hand (mfma_wait_loads).
-constexpr int kMQueue = 16;                // queue slots per wavefront
-constexpr int kMAhead = kMQueue - 2;       // loads in flight behind the unit being taken (at most kMAhead + 2 slots are in use)
-constexpr int kMSlotBytes = 2 * kMInCols * (int)sizeof(float);
-
-__device__ __forceinline__ void mfma_dma_unit(const float* p, unsigned lds_byte_address, unsigned long long lanes)
+// Loads from global memory straight into LDS: lane l's 16 (4) bytes land at M0 + 16 l (M0 + 4 l);
+// lanes switched off load nothing and write nothing.  The compiler does not see these loads as
+// such; the waits for them are written by hand.
+__device__ __forceinline__ void dma_b128(const float* p, unsigned lds_byte_address, unsigned long long lanes)
 {
     unsigned long long saved;
     asm volatile("s_mov_b64 %0, exec\n\t"
@@ -127,46 +109,73 @@ __device__ __forceinline__ void mfma_dma_unit(const float* p, unsigned lds_byte_
                  : "memory");
 }
 
-// Wait until at most `kMAhead` of the wavefront's vector-memory operations are outstanding.
-// Loads complete in the order they were issued, so a unit that kMAhead younger loads have
-// followed has arrived by then -- whatever stores are outstanding besides (they only make the
-// wait stricter).
-__device__ __forceinline__ void mfma_wait_loads()
+__device__ __forceinline__ void dma_b32(const float* p, unsigned lds_byte_address, unsigned long long lanes)
 {
-    static_assert(kMAhead == 14, "the wait below is written for 14 loads in flight");
-    asm volatile("s_waitcnt vmcnt(14)" ::: "memory");
+    unsigned long long saved;
+    asm volatile("s_mov_b64 %0, exec\n\t"
+                 "s_mov_b32 m0, %2\n\t"
+                 "s_mov_b64 exec, %3\n\t"
+                 "global_load_lds_dword %1, off\n\t"
+                 "s_mov_b64 exec, %0"
+                 : "=&s"(saved)
+                 : "v"(p), "s"(lds_byte_address), "s"(lanes)
+                 : "memory");
 }
 
-// Eight consecutive inputs, scaled and split as in mfma_split.
+// A wavefront fetches every fourth unit, with kLoads loads; kSAhead = 12 younger units follow
+// the one that must have arrived, three of them its own.  Vector-memory operations complete in
+// the order they were issued, so "at most 3 kLoads outstanding" says that unit has landed,
+// whatever stores are outstanding besides (they only make the wait stricter).
+template <int kLoads>
+__device__ __forceinline__ void wait_own_units()
+{
+    static_assert(kSAhead == 12 && (kLoads == 3 || kLoads == 5), "the waits below are written for three own units in flight");
+    if (kLoads == 3) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(15)" ::: "memory");
+}
+
+// Workgroup barrier and nothing else (no wait for outstanding memory operations: the loads in
+// flight must stay in flight).
+__device__ __forceinline__ void barrier_only()
+{
+    asm volatile("s_barrier" ::: "memory");
+}
+
+// Eight consecutive inputs times 2^13, split into fp16 hi and lo parts: v * 2^13 = hi + lo * 2^-11
+// (both rounded to nearest).  The remainder v * 2^13 - hi is exact in fp32 and at most half an
+// fp16 ulp of hi; stored 2^11 times larger it has the magnitude of hi at most and stays a normal
+// fp16 number whenever hi is one (the matrix cores treat subnormal fp16 inputs as zero).  A value
+// of 8 or more becomes infinite here and shows up as inf / NaN in the results it feeds.
 __device__ __forceinline__ void mfma_split8(const f4& a, const f4& b, h8& hi, h8& lo)
 {
-    const f4 sa = a * kMXScale, sb = b * kMXScale;
-    const h4 ha = __builtin_convertvector(sa, h4), hb = __builtin_convertvector(sb, h4);
-    const h4 la = __builtin_convertvector((sa - __builtin_convertvector(ha, f4)) * kMLoScale, h4);
-    const h4 lb = __builtin_convertvector((sb - __builtin_convertvector(hb, f4)) * kMLoScale, h4);
-    hi = __builtin_shufflevector(ha, hb, 0, 1, 2, 3, 4, 5, 6, 7);
-    lo = __builtin_shufflevector(la, lb, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
-// v * 2^13 = hi + lo * 2^-11 in fp16 (both rounded to nearest): the remainder v*2^13 - hi is
-// exact in fp32 and at most half an fp16 ulp of hi; stored 2^11 times larger it has the
-// magnitude of hi at most and stays a normal fp16 number whenever hi is one (the matrix
-// cores treat subnormal fp16 inputs as zero).  A value of 8 or more becomes infinite here
-// and shows up as inf / NaN in the results it feeds.
-__device__ __forceinline__ void mfma_split(const float (&v)[4], h4& hi, h4& lo)
-{
-    f4 s;
+    // Three instructions per element, spelled out (the compiler's own selection takes four):
+    // v_fma_mixlo/mixhi_f16 scale in fp32 and round once to fp16 into one half of a register,
+    // v_fma_mix_f32 takes v * 2^13 - hi with hi read as fp16 from either half (exact).
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    const float xs = kMXScale, ls = kMLoScale;
+    u4 hp, lp;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) s[i] = v[i] * kMXScale;
-    hi = __builtin_convertvector(s, h4);
-    lo = __builtin_convertvector((s - __builtin_convertvector(hi, f4)) * kMLoScale, h4);
+    for (int i = 0; i < 4; ++i) {
+        const float v0 = i < 2 ? a[2 * i] : b[2 * i - 4], v1 = i < 2 ? a[2 * i + 1] : b[2 * i - 3];
+        unsigned h, l;
+        float r0, r1;
+        asm("v_fma_mixlo_f16 %0, %1, %2, 0" : "=v"(h) : "v"(v0), "s"(xs));
+        asm("v_fma_mixhi_f16 %0, %1, %2, 0" : "+v"(h) : "v"(v1), "s"(xs));
+        asm("v_fma_mix_f32 %0, %1, %2, -%3 op_sel_hi:[0,0,1]" : "=v"(r0) : "v"(v0), "s"(xs), "v"(h));
+        asm("v_fma_mix_f32 %0, %1, %2, -%3 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "=v"(r1) : "v"(v1), "s"(xs), "v"(h));
+        asm("v_fma_mixlo_f16 %0, %1, %2, 0" : "=v"(l) : "v"(r0), "s"(ls));
+        asm("v_fma_mixhi_f16 %0, %1, %2, 0" : "+v"(l) : "v"(r1), "s"(ls));
+        hp[i] = h; lp[i] = l;
+    }
+    hi = __builtin_bit_cast(h8, hp);
+    lo = __builtin_bit_cast(h8, lp);
 }
 
-template <int NS>
-__global__ __launch_bounds__(kBlock) void conv2d_mfma_kernel(Taps2D taps, const float* __restrict__ x,
+template <int NS, int G>
+__global__ __launch_bounds__(G * kBlock) void conv2d_mfma_kernel(Taps2D taps, const float* __restrict__ x,
                                                              float* __restrict__ y, int w_img, long long xp,
                                                              int oh, int ow, long long yp, int kh, int kw,
-                                                             int rows, int row_blocks, int col_groups, int per_xcd,
+                                                             int rows, int row_blocks, int col_sets, int per_xcd,
                                                              float tap_scale, float inv_scale)
 {
     (void)taps;
@@ -175,13 +184,27 @@ __global__ __launch_bounds__(kBlock) void conv2d_mfma_kernel(Taps2D taps, const 
 
     // wtab[plane][jc][dr - jr + 3][dc] = hi / lo part of f[dr - jr][dc - jc] * tap_scale
     __shared__ __attribute__((aligned(16))) _Float16 wtab[2][4][TROWS][16];
-    // per wavefront: two unit buffers x (hi, lo) x 2 rows x 80 columns
-    __shared__ __attribute__((aligned(16))) _Float16 stage[kMWaves][2][2][2][kMInCols];
-    // per wavefront: queue of units as they come from memory, 2 rows x 80 columns of fp32 each
-    __shared__ __attribute__((aligned(16))) float queue[kMWaves][kMQueue][2][kMInCols];
+    __shared__ __attribute__((aligned(16))) float squeues[G][kSQueue][kSSlotFloats];
+
+    const int g = xcd_contiguous(blockIdx.x, per_xcd);
+    if (g >= row_blocks * col_sets) return;                                // (the whole workgroup)
+    const int rb = g / col_sets, cs = g - rb * col_sets;                   // workgroups walk along the rows of the image
+    const int wave_wg = wave_in_block();
+    const int grp = wave_wg / kMWaves, wave = wave_wg - grp * kMWaves;     // column group within the workgroup, wavefront within the group
+    const int c0g = (cs * G + grp) * kMGroupCols;
+    const bool beyond = c0g >= ow;                                         // uniform: a group of the last workgroup with no outputs
+    float (*squeue)[kSSlotFloats] = squeues[grp];
+    // Columns of the unit that lie inside the image: whole groups of four go with the 16-byte
+    // loads, up to three more ("fringe") one by one; the rest is never loaded and reads as 0.
+    const int in_cols = beyond ? 0 : min(w_img - c0g, kSCols);
+    const bool ragged = in_cols < kSCols;                                  // uniform: the column group at the right edge
+    if (ragged) {
+        f4* q4 = reinterpret_cast<f4*>(&squeue[0][0]);
+        for (int e = threadIdx.x & (kBlock - 1); e < kSQueue * kSSlotFloats / 4; e += kBlock) q4[e] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
 
     kernarg_floats taps_f = (kernarg_floats)__builtin_amdgcn_kernarg_segment_ptr();
-    for (int e = threadIdx.x; e < 4 * TROWS * 16; e += kBlock) {
+    for (int e = threadIdx.x; e < 4 * TROWS * 16; e += G * kBlock) {
         const int dc = e & 15, tr = (e >> 4) % TROWS, jc = e / (16 * TROWS);
         const int p = tr - 3, q = dc - jc;
         float v = 0.0f;
@@ -192,16 +215,12 @@ __global__ __launch_bounds__(kBlock) void conv2d_mfma_kernel(Taps2D taps, const 
     }
     __syncthreads();
 
-    const int g = xcd_contiguous(blockIdx.x, per_xcd);
-    if (g >= row_blocks * col_groups) return;
-    const int rb = g / col_groups, cg = g - rb * col_groups;               // workgroups walk along the rows of the image
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = wave_in_block();
-    const int c0 = (cg * kMWaves + wave) * kMOutCols;
-    if (c0 >= ow) return;
+    const int c0 = c0g + wave * kMOutCols;                                 // may lie beyond the image: such a strip stores nothing
     const int r0 = rb * rows;
     const int rows_out = min(rows, oh - r0);
     const int steps = (rows_out + 3) >> 2;
+    const int last_row = r0 + rows_out + kh - 2;                           // last input row the block needs
 
     const int i16 = lane & 15, kb = lane >> 4;                             // MFMA operand coordinates of the lane
 
@@ -217,146 +236,130 @@ __global__ __launch_bounds__(kBlock) void conv2d_mfma_kernel(Taps2D taps, const 
         }
     }
 
-    MfmaFetcher fetch;
-    fetch.rowp = x + (long long)r0 * xp;
-    fetch.xp = xp; fetch.w_img = w_img;
-    fetch.rows_left = rows_out + kh - 2;                                    // the block reads rows r0 .. r0 + rows_left
-    const int flane = lane < kMUnitLanes ? lane : lane - kMUnitLanes;     // lanes 40 .. 63 shadow lanes 0 .. 23
-    const int frow = flane >= 20 ? 1 : 0;
-    fetch.fcol = c0 + kTile * (flane - 20 * frow);
-    fetch.off_one = fetch.fcol;
-    fetch.off_two = fetch.fcol + (frow ? xp : 0);
-    const bool edge = c0 + kMInCols > w_img;
-
-    _Float16* const st_w = &stage[wave][0][0][frow][kTile * (flane - 20 * frow)];          // where the lane stages
-    const _Float16* const st_r = &stage[wave][0][0][kb >> 1][kTile * i16 + 8 * (kb & 1)];  // where its window starts
-    constexpr int kPlane = 2 * kMInCols, kBuf = 2 * kPlane;
-
     h8 bh[RS], bl[RS];                     // ring: unit u lives in slot u % RS
 
-    // ------------------------------------------------------------------- edge strips
-    // Strips that reach past the right edge of the image fetch through registers with per-lane
-    // bounds checks (columns outside the image read as 0), split in the 40 fetching lanes and hand
-    // the fp16 values to the other lanes through a wave-private staging buffer.  They are a small
-    // part of any large image, so nothing is kept in flight beyond the step at hand.
-    auto run_edge = [&]() {
-        float pre[2][4];
-        // stage the unit in pre[k] and read the lane's windows of it into ring slot `slot`
-        auto consume = [&](int k, int slot) {
-            {
-                h4 hi, lo;
-                mfma_split(pre[k], hi, lo);
-                *reinterpret_cast<h4*>(st_w + k * kBuf) = hi;              // (shadow lanes write the same values again)
-                *reinterpret_cast<h4*>(st_w + k * kBuf + kPlane) = lo;
+    // ------------------------------------------------------------------ fetching a unit
+    // Unit u = rows r0 + 2u and r0 + 2u + 1 (past the block's last row the last row is read
+    // again: that keeps the count of loads fixed, and what it brings in only feeds rows that are
+    // not stored).  Whole column groups: a 1 KB load per row and one of 8 lanes for the halo
+    // columns of both rows.  The ragged group: the same with the lanes beyond the image off,
+    // and two 4-byte loads for the fringes; a load that would have no lane left is replaced by
+    // a 4-byte load of an element inside the image into the slot's pad.
+    const unsigned q_base = (unsigned)(size_t)&squeue[0][0];               // LDS byte address of slot 0
+    const int full4 = in_cols >> 2;                                        // whole groups of four columns (0 .. 68)
+    const int fringe = in_cols & 3;                                        // (0 when the unit is whole: 272 = 4 * 68)
+    const int main4 = min(full4, kMGroupCols / 4), tail4 = full4 - main4;  // groups in the main part and in the halo part
+    const unsigned long long mask_main = main4 >= 64 ? ~0ull : (1ull << main4) - 1;
+    const unsigned long long mask_tail = ((1ull << tail4) - 1) * 0x11ull;  // lanes 0 .. 3: first row, 4 .. 7: second row
+    const unsigned long long mask_fringe = (1ull << fringe) - 1;
+    const unsigned fringe_at = (unsigned)shared_slot_offset(0, 4 * full4 < kSCols ? 4 * full4 : 0) * (unsigned)sizeof(float);
+    const unsigned fringe_row = (4 * full4 < kMGroupCols ? kMGroupCols : 16) * (unsigned)sizeof(float);   // first row -> second row
+    const long long off_main = c0g + kTile * lane;
+    const int tail_row = (lane >> 2) & 1;
+    const long long off_tail = c0g + kMGroupCols + kTile * (lane & 3);
+    const long long off_fringe = c0g + 4 * full4 + (lane & 3);
+
+    auto issue = [&](int u, auto ragged_tag) {                             // u is uniform
+        constexpr bool RAGGED = decltype(ragged_tag)::value;
+        if ((u & (kMWaves - 1)) != wave) return;
+        const int ra = min(r0 + 2 * u, last_row), rb2 = min(r0 + 2 * u + 1, last_row);
+        const float* pa = x + (long long)ra * xp;
+        const float* pb = x + (long long)rb2 * xp;
+        const unsigned slot = q_base + (unsigned)(u & (kSQueue - 1)) * kSSlotBytes;
+        if (!RAGGED) {
+            dma_b128(pa + off_main, slot, ~0ull);
+            dma_b128(pb + off_main, slot + kMGroupCols * (unsigned)sizeof(float), ~0ull);
+            dma_b128((tail_row ? pb : pa) + off_tail, slot + 2 * kMGroupCols * (unsigned)sizeof(float), 0xffull);
+        } else {
+            const unsigned pad = slot + kSPad * (unsigned)sizeof(float);
+            if (main4 > 0) {
+                dma_b128(pa + off_main, slot, mask_main);
+                dma_b128(pb + off_main, slot + kMGroupCols * (unsigned)sizeof(float), mask_main);
+            } else {
+                dma_b32(pa + c0g, pad, 1ull);
+                dma_b32(pb + c0g, pad, 1ull);
             }
-            // Other lanes of this wavefront read what was just written.  The hardware serves a
-            // wavefront's LDS accesses in order; all that is needed is that the compiler keeps
-            // the reads behind the writes.
-            asm volatile("" ::: "memory");
-            const h4 h0 = *reinterpret_cast<const h4*>(st_r + k * kBuf);
-            const h4 h1 = *reinterpret_cast<const h4*>(st_r + k * kBuf + 4);
-            const h4 l0 = *reinterpret_cast<const h4*>(st_r + k * kBuf + kPlane);
-            const h4 l1 = *reinterpret_cast<const h4*>(st_r + k * kBuf + kPlane + 4);
-            bh[slot] = __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7);
-            bl[slot] = __builtin_shufflevector(l0, l1, 0, 1, 2, 3, 4, 5, 6, 7);
-        };
-#pragma unroll
-        for (int u = 0; u < NS; ++u) {
-            fetch.template next<true>(pre[u & 1]);
-            consume(u & 1, u % RS);
-        }
-        const int col = c0 + kTile * i16;
-        for (int t0 = 0; t0 < steps; t0 += PERIOD) {
-#pragma unroll
-            for (int ph = 0; ph < PERIOD; ++ph) {
-                const int t = t0 + ph;
-                if (t >= steps) break;
-                fetch.template next<true>(pre[0]);
-                fetch.template next<true>(pre[1]);
-                f4 acc_hh = {0.0f, 0.0f, 0.0f, 0.0f}, acc_x = acc_hh;
-#pragma unroll
-                for (int s = 0; s < NS; ++s) {
-                    const int slot = (2 * ph + s) % RS;
-                    acc_x = __builtin_amdgcn_mfma_f32_16x16x32_f16(al[s], bh[slot], acc_x, 0, 0, 0);
-                    acc_hh = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[s], bh[slot], acc_hh, 0, 0, 0);
-                    acc_x = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[s], bl[slot], acc_x, 0, 0, 0);
-                }
-                // lane (i16, kb) holds outputs (row 4 t + kb, columns c0 + 4 i16 .. + 3)
-                if (4 * t + kb < rows_out) {
-                    float o[4];
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        o[v] = __builtin_fmaf(acc_x[v], inv_scale * (1.0f / kMLoScale), acc_hh[v] * inv_scale);
-                    store4_guarded(y + (long long)(r0 + 4 * t + kb) * yp, col, ow, o);
-                }
-                consume(0, (2 * ph + NS) % RS);
-                consume(1, (2 * ph + NS + 1) % RS);
+            if (tail4 > 0) dma_b128((tail_row ? pb : pa) + off_tail, slot + 2 * kMGroupCols * (unsigned)sizeof(float), mask_tail);
+            else dma_b32(pa + c0g, pad, 1ull);
+            if (fringe > 0) {
+                dma_b32(pa + off_fringe, slot + fringe_at, mask_fringe);
+                dma_b32(pb + off_fringe, slot + fringe_at + fringe_row, mask_fringe);
+            } else {
+                dma_b32(pa + c0g, pad, 1ull);
+                dma_b32(pb + c0g, pad, 1ull);
             }
         }
     };
 
-    // ---------------------------------------------------------------- interior strips
-    auto run_queued = [&]() {
-        const unsigned long long fetch_lanes = (1ull << kMUnitLanes) - 1;  // lanes 0 .. 39 fetch
-        const unsigned q_base = (unsigned)(size_t)&queue[wave][0][0][0];   // LDS byte address of slot 0
-        const float* const win = &queue[wave][0][kb >> 1][kTile * i16 + 8 * (kb & 1)];   // the lane's window in slot 0
-        int q_in = 0, q_out = 0;                                           // slots of the next unit in / out (uniform)
+    // --------------------------------------------------------- taking a unit into the ring
+    const int col_w = wave * kMOutCols + kTile * i16 + 8 * (kb & 1);       // the lane's window starts here (workgroup columns)
+    const float* const win_a = &squeue[0][0] + shared_slot_offset(kb >> 1, col_w);
+    const float* const win_b = &squeue[0][0] + shared_slot_offset(kb >> 1, col_w + 4);
+    int q_out = 0;                                                         // float offset of the oldest unit not taken yet
+    auto take = [&](int slot) {
+        const f4 a = *reinterpret_cast<const f4*>(win_a + q_out);
+        const f4 b = *reinterpret_cast<const f4*>(win_b + q_out);
+        mfma_split8(a, b, bh[slot], bl[slot]);
+        q_out = q_out + kSSlotFloats == kSQueue * kSSlotFloats ? 0 : q_out + kSSlotFloats;
+    };
 
-        auto issue = [&]() {
-            mfma_dma_unit(fetch.next_address(), q_base + q_in * kMSlotBytes, fetch_lanes);
-            q_in = q_in + 1 == kMQueue ? 0 : q_in + 1;
-        };
-        // the lane's 8-input window of the oldest queued unit -> ring slot
-        auto take = [&](int slot) {
-            const float* w8 = win + q_out * (kMSlotBytes / (int)sizeof(float));
-            const f4 a = *reinterpret_cast<const f4*>(w8);
-            const f4 b = *reinterpret_cast<const f4*>(w8 + 4);
-            mfma_split8(a, b, bh[slot], bl[slot]);
-            q_out = q_out + 1 == kMQueue ? 0 : q_out + 1;
-        };
+    const int col = c0 + kTile * i16;
+    const long long yoff = (long long)kb * yp + col;
 
-        // Units 0 .. NS-3 go into the ring before the first step; every step then starts by sending
-        // two more units on their way and taking in the two newest units it needs (2t+NS-2 and
-        // 2t+NS-1), which its last six instructions use -- their split overlaps the instructions
-        // that work on the older units.  kMAhead younger loads are in flight at every wait.
+    // Every step: the owners send units 2t + NS + 10 and 2t + NS + 11 on their way, every wavefront
+    // waits for its own loads of units <= 2t + NS - 1, a barrier makes them visible to all, and
+    // each lane takes its windows of units 2t + NS - 2 and 2t + NS - 1 into the ring.  The slot a
+    // unit goes to was last read two steps earlier, before the previous step's barrier.
+    auto run = [&](auto ragged_tag) {
+        constexpr bool RAGGED = decltype(ragged_tag)::value;
+        constexpr int kLoads = RAGGED ? 5 : 3;
 #pragma unroll 1
-        for (int u = 0; u < kMAhead; ++u) issue();
+        for (int u = 0; u < kSAhead; ++u) issue(u, ragged_tag);
 #pragma unroll
         for (int u = 0; u < NS - 2; ++u) {
-            issue();                                                       // unit u now has kMAhead younger loads behind it
-            mfma_wait_loads();
+            issue(kSAhead + u, ragged_tag);                                // unit u now has kSAhead younger units behind it
+            wait_own_units<kLoads>();
+            barrier_only();
             take(u % RS);
         }
-
-        const int col = c0 + kTile * i16;
-        const long long yoff = (long long)kb * yp + col;
 
         auto step = [&](int t, int ph, auto whole_tag) {
             constexpr bool WHOLE = decltype(whole_tag)::value;
             // nothing moves across a step's start (the scheduler would otherwise pull the first
             // instructions of later steps' splits up to here, in front of their waits)
             __builtin_amdgcn_sched_barrier(0);
-            issue();
-            issue();
-            mfma_wait_loads();
+            issue(2 * t + NS - 2 + kSAhead, ragged_tag);
+            issue(2 * t + NS - 1 + kSAhead, ragged_tag);
+            wait_own_units<kLoads>();
+            barrier_only();
             take((2 * ph + NS - 2) % RS);
             take((2 * ph + NS - 1) % RS);
-            f4 acc_hh = {0.0f, 0.0f, 0.0f, 0.0f}, acc_lh = acc_hh, acc_hl = acc_hh;
+            // hi*hi in one accumulator, the two cross terms (both 2^11 too large) in another
+            f4 acc_hh = {0.0f, 0.0f, 0.0f, 0.0f}, acc_x = acc_hh;
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 const int slot = (2 * ph + s) % RS;
+                acc_x = __builtin_amdgcn_mfma_f32_16x16x32_f16(al[s], bh[slot], acc_x, 0, 0, 0);
                 acc_hh = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[s], bh[slot], acc_hh, 0, 0, 0);
-                acc_lh = __builtin_amdgcn_mfma_f32_16x16x32_f16(al[s], bh[slot], acc_lh, 0, 0, 0);
-                acc_hl = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[s], bl[slot], acc_hl, 0, 0, 0);
+                acc_x = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[s], bl[slot], acc_x, 0, 0, 0);
             }
+            // lane (i16, kb) holds outputs (row 4 t + kb, columns c0 + 4 i16 .. + 3)
             if (WHOLE || 4 * t + kb < rows_out) {
-                f4u o4;
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    o4[v] = __builtin_fmaf(acc_lh[v] + acc_hl[v], inv_scale * (1.0f / kMLoScale), acc_hh[v] * inv_scale);
                 float* yr = y + (long long)(r0 + 4 * t) * yp;              // uniform; the lane's part is yoff
-                if (SYSCONV_NONTEMPORAL_STORE) __builtin_nontemporal_store(o4, reinterpret_cast<f4u*>(yr + yoff));
-                else *reinterpret_cast<f4u*>(yr + yoff) = o4;
+                if (!RAGGED) {
+                    f4u o4;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        o4[v] = __builtin_fmaf(acc_x[v], inv_scale * (1.0f / kMLoScale), acc_hh[v] * inv_scale);
+                    if (SYSCONV_NONTEMPORAL_STORE) __builtin_nontemporal_store(o4, reinterpret_cast<f4u*>(yr + yoff));
+                    else *reinterpret_cast<f4u*>(yr + yoff) = o4;
+                } else {
+                    float o[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        o[v] = __builtin_fmaf(acc_x[v], inv_scale * (1.0f / kMLoScale), acc_hh[v] * inv_scale);
+                    store4_guarded(yr + (long long)kb * yp, col, ow, o);
+                }
             }
         };
 
@@ -375,8 +378,14 @@ __global__ __launch_bounds__(kBlock) void conv2d_mfma_kernel(Taps2D taps, const 
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
 
-    if (edge) run_edge();
-    else run_queued();
+    if (beyond) {
+        // no outputs, no loads: only the barriers the other groups of the workgroup count on
+        for (int b = 0; b < NS - 2 + steps; ++b) barrier_only();
+    } else if (ragged) {
+        run(std::true_type{});
+    } else {
+        run(std::false_type{});
+    }
 }
 
 float largest_finite_magnitude(const float* f, int n)
@@ -389,8 +398,25 @@ float largest_finite_magnitude(const float* f, int n)
     return amax;
 }
 
-template <int NS>
-hipError_t launch_mfma(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw, float* y,
+// How many workgroups of the kernel the device the calling thread has current holds at once
+// (asked once per filter height class and device).
+template <int NS, int G>
+int resident_workgroups()
+{
+    static int cached[kMaxDevices];                                // 0: not asked yet
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    if (cached[dev] == 0) {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, conv2d_mfma_kernel<NS, G>, G * kBlock, 0) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cached[dev] = per_cu * cus;
+    }
+    return cached[dev];
+}
+
+template <int NS, int G>
+hipError_t launch_mfma_g(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw, float* y,
                        size_t yp, hipStream_t s)
 {
     Taps2D taps;
@@ -404,18 +430,34 @@ hipError_t launch_mfma(const float* x, int h, int w, size_t xp, const float* f, 
     const float inv_scale = 1.0f / (tap_scale * kMXScale);
 
     const int oh = h - kh + 1, ow = w - kw + 1;
-    const int col_groups = (ow + kMWaves * kMOutCols - 1) / (kMWaves * kMOutCols);
-    int rows = 64;
-    while (rows > 8 && (long long)((oh + rows - 1) / rows) * col_groups < 2048) rows >>= 1;
+    const int col_sets = (ow + G * kMGroupCols - 1) / (G * kMGroupCols);
+    // Row blocks sized so that the grid is one round of resident workgroups (or, when there are
+    // more column groups than places, one block per column group): every column group is cut
+    // into as many blocks as its share of the places allows, at least 8 rows each.
+    const int places = resident_workgroups<NS, G>();
+    if (places <= 0) return hipErrorInvalidConfiguration;
+    const int cuts = places / col_sets > 1 ? places / col_sets : 1;
+    const int quads = (oh + 3) / 4;
+    int rows = 4 * ((quads + cuts - 1) / cuts);
+    if (rows < 8) rows = 8;
     const int row_blocks = (oh + rows - 1) / rows;
-    const long long groups = (long long)row_blocks * col_groups;
+    const long long groups = (long long)row_blocks * col_sets;
     const long long per_xcd = (groups + kXcds - 1) / kXcds;
     const long long blocks = per_xcd * kXcds;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL(conv2d_mfma_kernel<NS>, dim3((unsigned)blocks), dim3(kBlock), 0, s, taps, x, y, w,
-                       (long long)xp, oh, ow, (long long)yp, kh, kw, rows, row_blocks, col_groups, (int)per_xcd,
+    hipLaunchKernelGGL((conv2d_mfma_kernel<NS, G>), dim3((unsigned)blocks), dim3(G * kBlock), 0, s, taps, x, y, w,
+                       (long long)xp, oh, ow, (long long)yp, kh, kw, rows, row_blocks, col_sets, (int)per_xcd,
                        tap_scale, inv_scale);
     return hipGetLastError();
+}
+
+constexpr int kMGroups = 3;                // column groups per workgroup: 12 wavefronts, one workgroup per CU
+
+template <int NS>
+hipError_t launch_mfma(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw, float* y,
+                       size_t yp, hipStream_t s)
+{
+    return launch_mfma_g<NS, kMGroups>(x, h, w, xp, f, kh, kw, y, yp, s);
 }
 
 }  // namespace

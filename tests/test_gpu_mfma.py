@@ -3,7 +3,8 @@
 Same metric and bound as every other projection, max |y - ref| / sum|f||x| <= 1e-5.  The path multiplies
 split fp16 operands (hi + lo, three products, fp32 sums), so on top of the usual cases the tests cover what is
 specific to it: the admissible input range |x| < 8, taps of any magnitude, the block structure (4 output rows x
-64 columns per instruction group, 2 input rows per fetched unit, a ring of 4 or 8 operand slots), and how
+64 columns per instruction group, column groups of 256 outputs fed from units of 2 rows x 272 columns, three
+column groups per workgroup, a ring of 4 or 8 operand slots, row blocks sized to the number of CUs), and how
 non-finite inputs spread.
 """
 import numpy as np
@@ -51,9 +52,9 @@ def test_mfma_random_all_sizes(kshape):
 
 @pytest.mark.parametrize("kk", [1, 3, 5, 8, 11, 13])
 def test_mfma_tall_images_cover_every_block_height(kk):
-    # The launcher gives a wavefront 64 output rows, fewer (down to 8) on images that would not yield 2048
-    # workgroups otherwise.  Tall, narrow images make every height run, ring wrap-around and the last short
-    # block included.
+    # The launcher cuts a column of the image into one row block per CU (a multiple of 4 rows, at least 8).
+    # Tall, narrow images run blocks of 68 .. 516 rows: many turns of the operand ring and of the 16-slot queue,
+    # and a last block that is shorter than the others.
     for oh in (2048 * 8 + 5, 2048 * 16 + 3, 2048 * 32 + 1, 2048 * 64 + 7):
         ow = 37
         h, w = oh + kk - 1, ow + kk - 1
@@ -61,6 +62,25 @@ def test_mfma_tall_images_cover_every_block_height(kk):
         y = run2d(x, f, "MFMA")
         e = err2d(y, x, f)
         assert e <= TOL, f"MFMA {kk}x{kk} image {h}x{w}: rel err {e}"
+
+
+@pytest.mark.parametrize("kshape", [(1, 1), (3, 1), (3, 2), (3, 3), (8, 5), (11, 11), (13, 13)])
+def test_mfma_right_edge_of_the_image(kshape):
+    # A column group's unit is 272 input columns: 64 + 4 groups of four, fetched 16 bytes per lane; what is left
+    # of a row beyond the last whole group of four (1 .. 3 columns) goes 4 bytes per lane, and nothing is loaded
+    # beyond the image.  Widths put the image's edge at every position mod 4 in the 256-column main part and in
+    # the 16-column halo part of the last group's unit, leave that group 1, 2 or 3 input columns only, and end
+    # the last workgroup (three column groups) after one, two and three groups.
+    kh, kw = kshape
+    h = kh + 21
+    for base in (0, 256, 512, 768, 1536):
+        for over in (1, 2, 3, 4, 5, 6, 7, 63, 130, 252, 253, 254, 255, 256):
+            ow = base + over                                   # the last group holds `over` output columns
+            w = ow + kw - 1
+            x, f = W.random_case(1000 * ow + kh, (h, w), (kh, kw), x_range=(0.0, 1.0))
+            y = run2d(x, f, "MFMA")
+            e = err2d(y, x, f)
+            assert e <= TOL, f"MFMA {kh}x{kw} image {h}x{w}: rel err {e}"
 
 
 @pytest.mark.parametrize("kshape", [(2, 2), (5, 5), (11, 11), (4, 6), (13, 13)])
