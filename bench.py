@@ -491,7 +491,7 @@ def main() -> int:
             achieved = 2 * issued_macs_per_output * w5.n_outputs / t / 1e12
             mf_traffic, mf_prov = _stored_traffic("conv2d_mfma_11x11_8k")
             result["roofline_mfma"] = {
-                "workload": "conv2d_8k_11x11", "projection": "MFMA", "kernel": f"conv2d_mfma_kernel<{ns}>",
+                "workload": "conv2d_8k_11x11", "projection": "MFMA", "kernel": f"conv2d_mfma_kernel<{ns}, 3>",
                 "bound": "mfma", "achieved": round(achieved, 1), "peak": 2500.0, "unit": "TFLOP/s",
                 "frac": round(achieved / 2500.0, 4),
                 "useful_fraction": round(w5.k_shape[0] * w5.k_shape[1] / issued_macs_per_output, 4),
