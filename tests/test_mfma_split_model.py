@@ -85,7 +85,7 @@ def test_split_fp16_three_products_meet_the_bound_with_margin(phase):
     x, f = _case((200, 300), (11, 11))
     ref, scale = oracle.conv2d(x, f), oracle.absdot2d(x, f)
     e = oracle.max_rel_err(_model(x, f, phase=phase), ref, scale)
-    assert e <= 3e-6 / 3, f"split-fp16 model: {e}"            # measured 9e-8: a margin of 100 under 1e-5
+    assert e <= 3e-6 / 3, f"split-fp16 model: {e}"            # measured 5e-8: a margin of 200 under 1e-5
 
 
 def test_signed_data_and_other_filter_sizes():
@@ -99,8 +99,8 @@ def test_signed_data_and_other_filter_sizes():
 def test_the_cross_terms_are_needed():
     x, f = _case((120, 200), (11, 11))
     ref, scale = oracle.conv2d(x, f), oracle.absdot2d(x, f)
-    assert oracle.max_rel_err(_model(x, f, products=("hh",)), ref, scale) > 1e-5          # fp16 alone: ~2e-4
-    assert oracle.max_rel_err(_model(x, f, products=("hh", "lh")), ref, scale) > 1e-5     # inputs unsplit: ~1e-4
+    assert oracle.max_rel_err(_model(x, f, products=("hh",)), ref, scale) > 1e-5          # fp16 alone: 1.1e-4
+    assert oracle.max_rel_err(_model(x, f, products=("hh", "lh")), ref, scale) > 1e-5     # inputs unsplit: 9e-5
 
 
 def test_small_inputs_need_the_enlarged_lo_parts():
