@@ -193,8 +193,9 @@ int sys_conv1d_stt(const float *d_x, size_t n,
  *   h_f      host, kh*kw floats row-major, 1 <= kh <= min(h, SYS_MAX_K2D), same for kw / w
  *   d_y      device, h-kh+1 rows of w-kw+1 floats, row stride y_pitch elements
  *            (>= w-kw+1); elements between rows are left untouched
- *   projection  AUTO and FBS accept every filter in range (AUTO: BFS for square filters
- *            up to 7x7, SBM for 8x8 .. 11x11, FBS otherwise); BFS and SBM are built
+ *   projection  AUTO and FBS accept every filter in range (AUTO, from measurements: square
+ *            filters up to 6x6 run FBS, or BFS where x_pitch * 4 is a power of two of at most
+ *            16 KB; 7x7 .. 11x11 run SBM; everything else FBS); BFS and SBM are built
  *            for SQUARE filters 2x2 .. 11x11 only (sys_conv2d_has) and return
  *            SYS_ERR_UNSUPPORTED otherwise; BSM, FSM and FFS are 1-D only.  FBS runs
  *            kernels specialised at compile time for every filter up to 7x7 (square or

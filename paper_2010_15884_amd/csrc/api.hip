@@ -177,11 +177,18 @@ int sys_conv2d(const float* d_x, int h, int w, size_t x_pitch, const float* h_f,
     if (ranges_overlap(d_x, x_bytes, d_y, y_bytes)) return SYS_ERR_ALIAS;
 
     int proj = projection;
-    // measured on MI355X: BFS (block form) wins up to 7x7, SBM from 8x8 on, FBS serves the rest
-    if (proj == SYS_PROJ_AUTO)
-        proj = (kh <= 7 && sysconv::has_conv2d_bfs(kh, kw)) ? SYS_PROJ_BFS
-             : sysconv::has_conv2d_sbm(kh, kw) ? SYS_PROJ_SBM
-             : sysconv::has_conv2d_bfs(kh, kw) ? SYS_PROJ_BFS : SYS_PROJ_FBS;
+    // Measured on MI355X, square images of 1000 .. 10240 columns (us, 5x5: BFS / SBM / FBS): 2996^2 15.8 / 14.3 / 14.3,
+    // 4092^2 25.9 / 28.7 / 27.1, 4604^2 33.9 / 36.4 / 32.5, 5996^2 57.2 / 57.0 / 51.1, 7164^2 81.0 / 83.6 / 75.1,
+    // 8188^2 103 / 104 / 95.5, 10236^2 166 / 170 / 155.  Up to 6x6 the FBS tile kernels win by 3 - 17 % except where
+    // the input pitch is a power of two of at most 16 KB (1024, 2048, 4096 columns): there single-strip order and the
+    // BFS block kernel's 1 KB-aligned strips win by 4 - 12 %.  7x7: SBM by 2 - 12 %.  8x8 .. 11x11: SBM.  The rest: FBS.
+    if (proj == SYS_PROJ_AUTO) {
+        const size_t pitch_bytes = x_pitch * sizeof(float);
+        const bool short_pow2_pitch = (pitch_bytes & (pitch_bytes - 1)) == 0 && pitch_bytes <= 16384;
+        if (kh == kw && kh >= 2 && kh <= 6) proj = short_pow2_pitch ? SYS_PROJ_BFS : SYS_PROJ_FBS;
+        else if (sysconv::has_conv2d_sbm(kh, kw) && kh >= 7) proj = SYS_PROJ_SBM;
+        else proj = SYS_PROJ_FBS;
+    }
     switch (proj) {
     case SYS_PROJ_FBS:
         return hip_status(sysconv::launch_conv2d_fbs(d_x, h, w, x_pitch, h_f, kh, kw, d_y, y_pitch, stream));

@@ -23,12 +23,14 @@ __device__ __forceinline__ int xcd_contiguous(int b, int per_xcd)
 //   - Workgroups are ordered strip after strip across a band of `side` strips, then one
 //     step down, and on to the next band when the bottom is reached.  side = 1 walks
 //     down single strips, which puts the pitch between all concurrent requests;
-//     side = 16 keeps long contiguous pieces of image rows in flight (band_width()).
+//     side = 16 keeps long contiguous pieces of image rows in flight, side >= strips is plain
+//     row-major order (band_width()).
 //   - Every XCD owns one contiguous run of workgroups in that order, so row blocks that
 //     share halo rows meet in one L2.
 // Returns false for a wavefront without work (uniform per wavefront).
 __device__ __forceinline__ void band_order(int g, int steps_down, int strips, int side, int& down, int& strip)
 {
+    side = min(side, strips);                                              // (whole rows: one band)
     const int per_band = side * steps_down;
     const int full = strips / side;                                        // bands of `side` strips
     const int band = min(g / per_band, full);
@@ -75,14 +77,22 @@ inline long long tile_workgroups_wide(int row_blocks, int strips, long long& per
 }
 
 // Strips per band, from in-process A/B runs on MI355X (block-form BFS, 5x5 unless noted;
-// us with 1 / 16 strips per band):
-//   pitch 16 KB (4096^2) 28.6 / 33.2, 20 KB 46 / 48, 24 KB and 28 KB level,
-//   pitch 32 KB (8192^2) 133 / 104 (SBM 150 / 116; 7x7 156 / 130), 48 KB level,
-//   pitch 64 KB (2048 x 16384) 59 / 46, (40960 x 16384) 1275 / 971,
-//   pitch 160 KB (16384 x 40960) 1320 / 1016 (2x2: 1289 / 969), pitch 2.5 MB 1117 / 1084;
-//   4 and 8 strips lie between.  Single strips win while the rows are short, bands as
-//   soon as walking down a strip strides over 32 KB or more.
-inline int band_width(size_t x_pitch) { return x_pitch * sizeof(float) >= 32768 ? 16 : 1; }
+// us with 1 / 16 strips per band / whole rows):
+//   pitch 16 KB (4096^2) 26.0 / 29.8 / 29.5, (8192 x 4096) 50 / 57 / 58, pitch 8 KB (16384 x 2048) 54 / 61 / 61,
+//   pitch 32 KB (8192^2) 130 / 101 / 98.5 (SBM 150 / 116; 7x7 156 / 130), (4096 x 8192) 65 / 53 / 58,
+//   pitch 64 KB (2048 x 16384) 78 / 52 / 60, (16384^2) 657 / 397 / 421, (40960 x 16384) 1275 / 971,
+//   pitch 18 KB (4608^2) 39.1 / 36.4 / 33.9, 20 KB 44.4 / 45.3 / 41.9, 28 KB 89.5 / 83.1 / 80.5, 40 KB 184 / 174 / 167,
+//   48 KB 260 / 241 / 236, 160 KB (16384 x 40960) 1381 / 1096 / 1085, 14 KB 24.8 / 22.7 / 22.7, 12 KB level;
+//   4 and 8 strips lie between.  Whole rows (plain row-major order) are best or level at every pitch
+//   tried that is not a power of two; at power-of-two pitches single strips win while the rows are
+//   short, bands of 16 from 32 KB on.
+constexpr int kWholeRows = 1 << 30;                                        // band_order() clamps to the strips there are
+inline int band_width(size_t x_pitch)
+{
+    const size_t bytes = x_pitch * sizeof(float);
+    if ((bytes & (bytes - 1)) != 0) return kWholeRows;
+    return bytes >= 32768 ? 16 : 1;
+}
 
 // Workgroups a launch of such a kernel needs (a multiple of the XCD count) and the
 // length of an XCD's run.
