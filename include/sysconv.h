@@ -198,8 +198,9 @@ int sys_conv1d_stt(const float *d_x, size_t n,
  *            16 KB; 7x7 .. 11x11 run SBM; everything else FBS); BFS and SBM are built
  *            for SQUARE filters 2x2 .. 11x11 only (sys_conv2d_has) and return
  *            SYS_ERR_UNSUPPORTED otherwise; BSM, FSM and FFS are 1-D only.  FBS runs
- *            kernels specialised at compile time for every filter up to 7x7 (square or
- *            not) and for single rows and columns (1 x k, k x 1, k <= 11: the two passes of a
+ *            kernels specialised at compile time for every filter of up to 11 rows and
+ *            columns whose smaller side is at most 7 (square or not; this includes single
+ *            rows and columns, 1 x k and k x 1: the two passes of a
  *            separable filter, which run at the rate of a plain copy), and a kernel with
  *            run-time filter sizes otherwise.
  *   h, w     at most INT_MAX - 2048 (SYS_ERR_UNSUPPORTED beyond; pitches at most 2^31).

@@ -7,7 +7,7 @@
 // not overlap and fetch the kw-1 columns to their right separately.
 //
 //   conv2d_fbs_kernel<RPW>            any kh, kw <= 15: LDS tile, one 1-D FBS pass per filter row
-//   conv2d_fbs_static_kernel<KH,KW,R> kh, kw <= 7, 1 x k and k x 1 up to k = 11: the same array with the sizes known
+//   conv2d_fbs_static_kernel<KH,KW,R> kh, kw <= 11 with min(kh, kw) <= 7: the same array with the sizes known
 //                                     at compile time and each staged row's window shared by the rows it feeds
 //   conv2d_bfs_block_kernel<K,K,ROWS> 2x2 .. 7x7: short row block, all loads up front
 //   conv2d_bfs_kernel<K,K,PD>         8x8 .. 11x11: strip walk with rows in flight
@@ -822,15 +822,17 @@ hipError_t launch_fbs_static(const float* x, int h, int w, size_t xp, const floa
 
 }  // namespace
 
-// Filters whose size is known at compile time: every kh x kw with 2 <= kh, kw <= 7, single rows
-// 1 x 2..11 and single columns 2..11 x 1 (the two passes of a separable filter).  From 8x8 on the taps no longer
+// Filters whose size is known at compile time: every kh x kw with 2 <= kh, kw <= 11 of which at
+// least one is at most 7 (4096^2, us, this kernel / the run-time-sized one: 9x3 29.9 / 40.4, 3x9 27.5 / 32.7,
+// 11x5 41.2 / 51.0, 5x11 43.7 / 45.2, 10x4 36.3 / 48.5, 7x11 56.5 / 57.0), single rows 1 x 2..11 and
+// single columns 2..11 x 1 (the two passes of a separable filter).  From 8x8 on the taps no longer
 // fit the scalar registers and the unrolled form loses to the run-time-sized kernel (11x11 on
 // 8192^2: 353 us with 4 rows per wavefront, 423 us with 2, against 313 us).  Output rows per wavefront
 // from a sweep on MI355X (us with 1 / 2 / 3 / 4 rows): 4096^2 3x3 27.1 / 26.4 / 28.0 / 28.2,
 // 5x5 32.3 / 27.7 / 28.1 / 29.6, 7x7 51.7 / 41.2 / 42.1 / 39.6; 8192^2 5x5 115.5 / 95.3 / 96.8 / 102.2.
 bool has_conv2d_fbs_static(int kh, int kw)
 {
-    if (kh >= 2 && kh <= 7 && kw >= 2 && kw <= 7) return true;
+    if (kh >= 2 && kh <= 11 && kw >= 2 && kw <= 11 && (kh <= 7 || kw <= 7)) return true;
     return (kh == 1 && kw >= 2 && kw <= 11) || (kw == 1 && kh >= 2 && kh <= 11);
 }
 
@@ -841,13 +843,20 @@ namespace {
 hipError_t launch_fbs_static_any(const float* x, int h, int w, size_t xp, const float* f, int kh, int kw, float* y,
                                  size_t yp, hipStream_t s)
 {
-    // 2 <= kh, kw <= 7: two output rows per wavefront up to 5 filter rows, four from 6 on (the sweep above)
+    // two output rows per wavefront up to 5 filter rows, four from 6 on (the sweep above)
 #define SYSCONV_FBS_STATIC_ROW(KH, RPW)                                                                     \
     SYSCONV_FBS_STATIC(KH, 2, RPW); SYSCONV_FBS_STATIC(KH, 3, RPW); SYSCONV_FBS_STATIC(KH, 4, RPW);       \
     SYSCONV_FBS_STATIC(KH, 5, RPW); SYSCONV_FBS_STATIC(KH, 6, RPW); SYSCONV_FBS_STATIC(KH, 7, RPW)
     SYSCONV_FBS_STATIC_ROW(2, 2); SYSCONV_FBS_STATIC_ROW(3, 2); SYSCONV_FBS_STATIC_ROW(4, 2);
     SYSCONV_FBS_STATIC_ROW(5, 2); SYSCONV_FBS_STATIC_ROW(6, 4); SYSCONV_FBS_STATIC_ROW(7, 4);
+    SYSCONV_FBS_STATIC_ROW(8, 4); SYSCONV_FBS_STATIC_ROW(9, 4); SYSCONV_FBS_STATIC_ROW(10, 4); SYSCONV_FBS_STATIC_ROW(11, 4);
 #undef SYSCONV_FBS_STATIC_ROW
+#define SYSCONV_FBS_STATIC_WIDE(KH, RPW)                                                                    \
+    SYSCONV_FBS_STATIC(KH, 8, RPW); SYSCONV_FBS_STATIC(KH, 9, RPW); SYSCONV_FBS_STATIC(KH, 10, RPW);      \
+    SYSCONV_FBS_STATIC(KH, 11, RPW)
+    SYSCONV_FBS_STATIC_WIDE(2, 2); SYSCONV_FBS_STATIC_WIDE(3, 2); SYSCONV_FBS_STATIC_WIDE(4, 2);
+    SYSCONV_FBS_STATIC_WIDE(5, 2); SYSCONV_FBS_STATIC_WIDE(6, 4); SYSCONV_FBS_STATIC_WIDE(7, 4);
+#undef SYSCONV_FBS_STATIC_WIDE
     SYSCONV_FBS_STATIC(1, 2, 4); SYSCONV_FBS_STATIC(1, 3, 4); SYSCONV_FBS_STATIC(1, 4, 4); SYSCONV_FBS_STATIC(1, 5, 4);
     SYSCONV_FBS_STATIC(1, 6, 4); SYSCONV_FBS_STATIC(1, 7, 4); SYSCONV_FBS_STATIC(1, 8, 4); SYSCONV_FBS_STATIC(1, 9, 4);
     SYSCONV_FBS_STATIC(1, 10, 4); SYSCONV_FBS_STATIC(1, 11, 4);

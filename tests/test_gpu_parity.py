@@ -134,11 +134,12 @@ def test_conv2d_single_row_and_single_column_filters(k):
         assert np.array_equal(run2d(xi, fi, "FBS").astype(np.float64), oracle.conv2d(xi, fi)), f"{kh}x{kw}"
 
 
-@pytest.mark.parametrize("kh", range(2, 8))
-def test_conv2d_every_rectangular_filter_up_to_7x7(kh):
-    # all kh x kw with 2 <= kh, kw <= 7 have an FBS kernel sized at compile time (2 output rows per wavefront up to
-    # 5 filter rows, 4 from 6 on: workgroups of 8 or 16 output rows); one image with a ragged last tile and strip each
-    for kw in range(2, 8):
+@pytest.mark.parametrize("kh", range(2, 12))
+def test_conv2d_every_rectangular_filter_with_a_compile_time_kernel(kh):
+    # all kh x kw up to 11 x 11 whose smaller side is at most 7 have an FBS kernel sized at compile time (2 output
+    # rows per wavefront up to 5 filter rows, 4 from 6 on: workgroups of 8 or 16 output rows); one image with a
+    # ragged last tile and strip each
+    for kw in range(2, 12 if kh <= 7 else 8):
         cols = 4 * (64 - (kw + 2) // 4)
         for (h, w) in [(kh + 16, kw + cols), (kh + 41, 2 * cols + kw + 2)]:
             x, f = W.random_case(h * 77 + w + 13 * kh + kw, (h, w), (kh, kw), x_range=(-1.0, 1.0))
