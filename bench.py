@@ -22,6 +22,8 @@ single JSON line printed at the end carries
                2 x multiply-adds / kernel time against the 78.6 TFLOP/s fp32 vector peak
   roofline_mfma that workload through the opt-in matrix-core projection: issued MFMA flops against
                the 2.5 PFLOP/s dense fp16 peak, with the fraction of them the definition needs
+  roofline_2d  the 4096^2, 5x5 workload (bound by HBM): its fastest projection against the 8 TB/s peak, with the
+               output rows packed tightly and on 128-byte lines
   cpu_baseline the CPU oracle (plain C, fp64) timed here on the host cores
   also         all five workloads and every projection built for them, each with
                GB/s, Gtap/s and its fraction of the HBM and fp32-FMA peaks, a plain
@@ -525,6 +527,25 @@ def main() -> int:
                 "kernel_us_mean": r["kernel_us_mean"],
                 "note": "v_mfma_f32_16x16x32_f16 on split fp16 operands (3 products); useful_fraction = kh*kw "
                         "multiply-adds of the definition / multiply-adds issued (Toeplitz zeros and the split)"}
+
+        # the large 2-D workload that is bound by HBM: its own roofline object (best projection, tight and aligned pitch)
+        c4 = [r for r in also if r["workload"] == "conv2d_4k_5x5" and r["projection"] != "MFMA"]
+        if c4:
+            tight = min((r for r in c4 if "y_pitch_floats" not in r), key=lambda r: r["kernel_us_mean"])
+            kern = {"BFS": "conv2d_bfs_block_kernel<5, 5, 2>", "SBM": "conv2d_sbm_block_kernel<5, 5, 4>",
+                    "FBS": "conv2d_fbs_static_kernel<5, 5, 2>"}[tight["projection"]]
+            t_traffic, t_prov = _stored_traffic(f"conv2d_{tight['projection'].lower()}_5x5_4k")
+            obj = {"workload": "conv2d_4k_5x5", "projection": tight["projection"], "kernel": kern, "bound": "hbm",
+                   "achieved": tight["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": tight["frac_hbm_peak"],
+                   "traffic": t_traffic, "traffic_source": t_prov, "kernel_us_mean": tight["kernel_us_mean"],
+                   "frac_of_copy": tight["frac_of_copy"]}
+            al = [r for r in c4 if "y_pitch_floats" in r]
+            if al:
+                obj["aligned_output_pitch"] = {"y_pitch_floats": al[0]["y_pitch_floats"], "projection": al[0]["projection"],
+                                               "achieved": al[0]["GB/s"], "frac": al[0]["frac_hbm_peak"],
+                                               "frac_of_copy": al[0]["frac_of_copy"],
+                                               "kernel_us_mean": al[0]["kernel_us_mean"]}
+            result["roofline_2d"] = obj
 
     # ---------------------------------------------------------- CPU baseline
     if not args.no_cpu:
